@@ -1,0 +1,212 @@
+/*
+ * attncache.h -- C ABI of the MI355X (gfx950) AttnCache hot path.
+ *
+ * The library implements, on one GPU, the data-parallel part of AttnCache
+ * (arXiv 2510.25979): similarity search over the feature-vector database,
+ * reuse of a cached attention map (O = A_cached . V) and the exact causal
+ * attention that serves queries without a hit.
+ *
+ * General rules
+ *   - Plain C.  Every pointer argument says whether it is DEVICE memory
+ *     (hipMalloc'd, e.g. a torch CUDA tensor's data_ptr()) or HOST memory.
+ *   - Every function returns an int32_t status: AC_OK (0) or a negative
+ *     AC_ERR_* code.  Nothing throws, aborts or prints.
+ *   - All GPU work is enqueued asynchronously on the caller's stream
+ *     (`stream` is a hipStream_t passed as void*; NULL = the default
+ *     stream).  A status covers argument validation and launch errors only.
+ *   - The library never allocates or frees device memory.  Inputs, outputs,
+ *     workspace and staging memory are owned by the caller; a database
+ *     handle borrows the pointers it is given and the caller keeps that
+ *     memory alive and unmodified until attncache_destroy_db().
+ *   - Tensors are dense, row-major, innermost index last, no padding.
+ *     Every tensor base pointer must be 16-byte aligned.
+ *   - Notation: B queries, N database feature vectors of dimension E,
+ *     M map entries, L layers, Hq query heads, Hkv key/value heads
+ *     (g = Hq / Hkv, query head h uses value head h / g), sequence length S,
+ *     head dimension D.
+ */
+#ifndef ATTNCACHE_H
+#define ATTNCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ------------------------------------------------------ */
+#define AC_OK 0
+#define AC_ERR_NULL -1      /* a required pointer is NULL                      */
+#define AC_ERR_SHAPE -2     /* a size is non-positive or unsupported           */
+#define AC_ERR_DTYPE -3     /* unknown / unsupported element type or metric    */
+#define AC_ERR_ALIGN -4     /* pointer not 16-byte aligned                     */
+#define AC_ERR_K_RANGE -5   /* k outside 1..min(AC_MAX_K, N)                   */
+#define AC_ERR_WORKSPACE -6 /* workspace / staging buffer too small            */
+#define AC_ERR_INDEX -7     /* a hit index is outside [-1, M)                  */
+#define AC_ERR_HIP -8       /* a HIP call failed, see attncache_last_hip_error */
+#define AC_ERR_MEMSPACE -9  /* pointer is not in the memory space it must be   */
+
+/* ---- element types, metrics ------------------------------------------- */
+#define AC_F32 0
+#define AC_F16 1  /* IEEE binary16 (feature vectors)                         */
+#define AC_BF16 2 /* bfloat16 (maps, Q, K, V, O)                             */
+
+#define AC_IP 0 /* similarity = inner product                               */
+#define AC_L2 1 /* score = -||q - e||^2, similarity = 1 - ||q - e||          */
+
+#define AC_MAX_K 64
+
+/* ---- database ---------------------------------------------------------- */
+
+/*
+ * Description of the two stores of the paper's "Databases" paragraph
+ * (Sec. 3.1): the feature-vector store that is searched and the
+ * attention-map store that is fetched from.  Both share one index; when
+ * several feature vectors refer to one map entry the optional table map_of
+ * gives the entry of each vector.
+ *
+ * Supported: emb_dtype AC_F16 with metric AC_IP and emb_dim % 16 == 0
+ * (matrix-core path), or emb_dtype AC_F32 with either metric and any emb_dim
+ * (vector-ALU path).  map_dtype AC_BF16 with seq_len % 32 == 0 and head_dim
+ * 64 or 128 (matrix-core path), or map_dtype AC_F32 with any seq_len and
+ * head_dim <= 256 (vector-ALU path).  n_q_heads % n_kv_heads == 0.
+ */
+typedef struct {
+  int32_t n_emb;        /* N: feature vectors                                */
+  int32_t emb_dim;      /* E                                                  */
+  int32_t emb_dtype;    /* AC_F16 | AC_F32                                    */
+  int32_t metric;       /* AC_IP | AC_L2                                      */
+  int32_t n_entries;    /* M: map entries                                     */
+  int32_t n_layers;     /* L                                                  */
+  int32_t n_q_heads;    /* Hq                                                 */
+  int32_t n_kv_heads;   /* Hkv                                                */
+  int32_t head_dim;     /* D                                                  */
+  int32_t seq_len;      /* S                                                  */
+  int32_t map_dtype;    /* AC_BF16 | AC_F32                                   */
+  int32_t causal;       /* 1: every map is exactly 0 above the diagonal and
+                           those blocks are never read; 0: dense maps        */
+  int32_t maps_on_host; /* 0: maps is DEVICE memory; 1: pinned HOST memory   */
+} attncache_db_desc;
+
+typedef struct attncache_db attncache_db; /* opaque, host-side */
+
+/*
+ * Bytes of DEVICE workspace attncache_search needs for up to max_batch
+ * queries and top-k.  Written to *out.
+ */
+int32_t attncache_workspace_bytes(const attncache_db_desc *desc,
+                                  int32_t max_batch, int32_t k, size_t *out);
+
+/*
+ * Store step of database building (Fig. 3, step 3): bind finished feature
+ * vectors and attention maps into one searchable handle.
+ *
+ *   emb       DEVICE [N][E] of emb_dtype.
+ *   map_of    DEVICE [N] int32 with values in [0, M), or NULL for the
+ *             identity (requires N == M): map entry of each feature vector.
+ *   maps      [M][L][Hq][S][S] of map_dtype; DEVICE, or pinned HOST memory
+ *             (hipHostMalloc) when desc->maps_on_host.  Each row of each map
+ *             sums to 1; with desc->causal the part above the diagonal is 0.
+ *             One entry is one contiguous block (all layers of one item lie
+ *             together, as the paper's layer-adjacent layout).
+ *   staging   DEVICE ring buffer of staging_bytes, used only when
+ *             maps_on_host; must hold at least two entries
+ *             (2 * L*Hq*S*S*sizeof(map element)).  NULL / 0 otherwise.
+ *   side_stream  hipStream_t on which host-to-device map copies are issued;
+ *             used only when maps_on_host (must differ from the stream
+ *             later passed to attncache_apply).
+ *   out       receives the handle (host malloc; free with destroy).
+ *
+ * Validates sizes, types, alignment and the memory space of each pointer
+ * (so a host pointer can never reach a kernel).  Copies nothing.
+ */
+int32_t attncache_build_db(const attncache_db_desc *desc, const void *emb,
+                           const int32_t *map_of, const void *maps,
+                           void *staging, size_t staging_bytes,
+                           void *side_stream, attncache_db **out);
+
+/* Releases the handle (and the events of the host-resident path).  The
+ * caller must have synchronised the streams the handle was used on. */
+int32_t attncache_destroy_db(attncache_db *db);
+
+/*
+ * Algorithm 1, search and threshold steps: exact top-k of the similarity
+ * between each query and every database feature vector, then hit / miss
+ * routing.
+ *
+ *   q         DEVICE [B][E] of the database's emb_dtype.
+ *   k         1..min(AC_MAX_K, N).
+ *   threshold theta: a query is a hit when the similarity of its best match
+ *             is >= theta (compared in fp32).
+ *   idx       DEVICE [B][k] int32 out: database rows, best first; equal
+ *             scores are ordered by ascending row index.
+ *   score     DEVICE [B][k] float out: fp32 scores (see AC_IP / AC_L2).
+ *   hit       DEVICE [B] int32 out: map entry (map_of[idx[b][0]]) for a hit,
+ *             -1 for a miss.
+ *   ws        DEVICE workspace of ws_bytes >= attncache_workspace_bytes().
+ *
+ * B == 0 is a no-op.  Scores are accumulated in fp32.
+ */
+int32_t attncache_search(const attncache_db *db, const void *q, int32_t B,
+                         int32_t k, float threshold, int32_t *idx,
+                         float *score, int32_t *hit, void *ws, size_t ws_bytes,
+                         void *stream);
+
+/*
+ * Algorithm 2, reuse branch: O[b][l][h] = A[hit[b]][layer_begin+l][h] . V[b][l][h/g]
+ * for l in [0, layer_count).  The maps are read in place from the database
+ * (no gather copy) when they live in device memory.
+ *
+ *   hit       [B] int32 entry per query, -1 = miss.  DEVICE memory when the
+ *             maps are in device memory; HOST memory when maps_on_host (the
+ *             host schedules one copy per distinct entry and the indices
+ *             are range-checked, AC_ERR_INDEX).
+ *   V         DEVICE [B][layer_count][Hkv][S][D], element type = map_dtype.
+ *   O         DEVICE [B][layer_count][Hq][S][D], element type = map_dtype.
+ *             Rows of misses (hit[b] == -1) are not written.
+ *
+ * Device-resident maps: hit values outside [-1, M) are treated as misses by
+ * the kernel (never dereferenced).  Host-resident maps: copies run on the
+ * side stream into the staging ring and are overlapped with the products on
+ * `stream`; on return all work is enqueued, nothing is waited for.
+ * fp32 accumulation; bf16 results are rounded once (nearest even).
+ */
+int32_t attncache_apply(const attncache_db *db, const int32_t *hit,
+                        const void *V, void *O, int32_t B, int32_t layer_begin,
+                        int32_t layer_count, void *stream);
+
+/*
+ * Algorithm 2, recompute branch with the map of Sec. 4:
+ * O = softmax(scale * Q K^T) V per (batch item, head); with causal != 0 keys
+ * j > i are excluded.  Flash-style: the S x S map is never written.
+ *
+ *   Q         DEVICE [B][Hq][S][D]; K, V DEVICE [B][Hkv][S][D]; O DEVICE
+ *             [B][Hq][S][D]; all of element type dtype (AC_BF16: S % 32 == 0,
+ *             D 64 or 128; AC_F32: any S, D <= 256).  Q and K are taken as
+ *             given (position encoding already applied).
+ *   row_sel   NULL, or DEVICE [B] int32: items with row_sel[b] >= 0 are
+ *             skipped and their O rows not written -- pass the hit array of
+ *             attncache_search to compute only the misses.
+ *   scale     0 selects 1/sqrt(D).
+ *
+ * Softmax statistics and accumulators are fp32.
+ */
+int32_t attention_exact(const void *Q, const void *K, const void *V, void *O,
+                        const int32_t *row_sel, int32_t B, int32_t Hq,
+                        int32_t Hkv, int32_t S, int32_t D, int32_t dtype,
+                        int32_t causal, float scale, void *stream);
+
+/* Short constant description of a status code. */
+const char *attncache_status_string(int32_t status);
+
+/* hipError_t (as int) of the last failed HIP call on this thread, 0 if none. */
+int32_t attncache_last_hip_error(void);
+
+/* Library version, major * 1000 + minor. */
+int32_t attncache_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATTNCACHE_H */
