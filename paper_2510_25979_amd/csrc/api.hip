@@ -1,0 +1,292 @@
+// C ABI of the library (see include/attncache.h): argument validation, the
+// database handle, and the host-side schedule of the pinned-host map path.
+// No kernel lives here.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/attncache.h"
+#include "launch.hpp"
+
+namespace {
+
+thread_local int32_t g_last_hip_error = 0;
+
+int32_t hip_fail(hipError_t e) {
+  g_last_hip_error = (int32_t)e;
+  (void)hipGetLastError();   // clear the sticky error so later calls are not blamed for it
+  return AC_ERR_HIP;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// 0 = device, 1 = pinned host, -1 = neither / unknown
+int memspace(const void* p) {
+  hipPointerAttribute_t attr;
+  hipError_t e = hipPointerGetAttributes(&attr, p);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return -1;
+  }
+  if (attr.type == hipMemoryTypeDevice) return 0;
+  if (attr.type == hipMemoryTypeHost) return 1;
+  return -1;
+}
+
+size_t elt_size(int32_t dtype) { return dtype == AC_F32 ? 4 : 2; }
+
+int32_t check_desc(const attncache_db_desc* d) {
+  if (!d) return AC_ERR_NULL;
+  if (d->n_emb < 1 || d->emb_dim < 1 || d->n_entries < 1 || d->n_layers < 1 || d->n_q_heads < 1 ||
+      d->n_kv_heads < 1 || d->head_dim < 1 || d->seq_len < 1)
+    return AC_ERR_SHAPE;
+  if (d->n_q_heads % d->n_kv_heads != 0) return AC_ERR_SHAPE;
+  if (d->metric != AC_IP && d->metric != AC_L2) return AC_ERR_DTYPE;
+  if (d->emb_dtype == AC_F16) {
+    if (d->emb_dim % 8 != 0) return AC_ERR_SHAPE;   // 16-byte rows
+  } else if (d->emb_dtype != AC_F32) {
+    return AC_ERR_DTYPE;
+  }
+  if (d->map_dtype == AC_BF16) {
+    if (d->seq_len % 32 != 0) return AC_ERR_SHAPE;
+    if (d->head_dim != 64 && d->head_dim != 128) return AC_ERR_SHAPE;
+  } else if (d->map_dtype == AC_F32) {
+    if (d->head_dim > 256) return AC_ERR_SHAPE;
+  } else {
+    return AC_ERR_DTYPE;
+  }
+  return AC_OK;
+}
+
+}  // namespace
+
+struct attncache_db {
+  attncache_db_desc d;
+  const void* emb;
+  const int32_t* map_of;
+  const void* maps;
+  // pinned-host path
+  unsigned char* staging;
+  size_t entry_bytes;
+  int n_slots;
+  int next_slot;
+  hipStream_t side;
+  std::vector<hipEvent_t> copied;     // per slot: host-to-device copy finished
+  std::vector<hipEvent_t> consumed;   // per slot: last product reading the slot finished
+  std::vector<char> used;             // per slot: consumed[] has been recorded at least once
+};
+
+extern "C" {
+
+int32_t attncache_version(void) { return 1000; }
+
+int32_t attncache_last_hip_error(void) { return g_last_hip_error; }
+
+const char* attncache_status_string(int32_t s) {
+  switch (s) {
+    case AC_OK: return "ok";
+    case AC_ERR_NULL: return "required pointer is NULL";
+    case AC_ERR_SHAPE: return "size is non-positive or unsupported";
+    case AC_ERR_DTYPE: return "unsupported element type or metric";
+    case AC_ERR_ALIGN: return "pointer is not 16-byte aligned";
+    case AC_ERR_K_RANGE: return "k outside 1..min(AC_MAX_K, N)";
+    case AC_ERR_WORKSPACE: return "workspace or staging buffer too small";
+    case AC_ERR_INDEX: return "hit index outside [-1, M)";
+    case AC_ERR_HIP: return "HIP call failed";
+    case AC_ERR_MEMSPACE: return "pointer is in the wrong memory space";
+    default: return "unknown status";
+  }
+}
+
+int32_t attncache_workspace_bytes(const attncache_db_desc* desc, int32_t max_batch, int32_t k,
+                                  size_t* out) {
+  if (!out) return AC_ERR_NULL;
+  int32_t rc = check_desc(desc);
+  if (rc != AC_OK) return rc;
+  if (max_batch < 0) return AC_ERR_SHAPE;
+  if (k < 1 || k > AC_MAX_K || k > desc->n_emb) return AC_ERR_K_RANGE;
+  *out = ac::search_workspace_bytes(desc->n_emb, desc->emb_dim, max_batch, k,
+                                    desc->emb_dtype == AC_F16);
+  return AC_OK;
+}
+
+int32_t attncache_build_db(const attncache_db_desc* desc, const void* emb, const int32_t* map_of,
+                           const void* maps, void* staging, size_t staging_bytes,
+                           void* side_stream, attncache_db** out) {
+  if (!out) return AC_ERR_NULL;
+  *out = nullptr;
+  int32_t rc = check_desc(desc);
+  if (rc != AC_OK) return rc;
+  if (!emb || !maps) return AC_ERR_NULL;
+  if (!map_of && desc->n_emb != desc->n_entries) return AC_ERR_SHAPE;
+  if (!aligned16(emb) || !aligned16(maps) || (map_of && !aligned16(map_of))) return AC_ERR_ALIGN;
+  if (memspace(emb) != 0) return AC_ERR_MEMSPACE;
+  if (map_of && memspace(map_of) != 0) return AC_ERR_MEMSPACE;
+  if (memspace(maps) != (desc->maps_on_host ? 1 : 0)) return AC_ERR_MEMSPACE;
+
+  attncache_db* db = new (std::nothrow) attncache_db();
+  if (!db) return AC_ERR_HIP;
+  db->d = *desc;
+  db->emb = emb;
+  db->map_of = map_of;
+  db->maps = maps;
+  db->staging = nullptr;
+  db->n_slots = 0;
+  db->next_slot = 0;
+  db->side = nullptr;
+  db->entry_bytes = (size_t)desc->n_layers * desc->n_q_heads * desc->seq_len * desc->seq_len *
+                    elt_size(desc->map_dtype);
+  if (desc->maps_on_host) {
+    if (!staging) { delete db; return AC_ERR_NULL; }
+    if (!aligned16(staging)) { delete db; return AC_ERR_ALIGN; }
+    if (memspace(staging) != 0) { delete db; return AC_ERR_MEMSPACE; }
+    if (staging_bytes / db->entry_bytes < 2) { delete db; return AC_ERR_WORKSPACE; }
+    db->staging = reinterpret_cast<unsigned char*>(staging);
+    db->n_slots = (int)std::min<size_t>(staging_bytes / db->entry_bytes, 64);
+    db->side = reinterpret_cast<hipStream_t>(side_stream);
+    db->copied.resize(db->n_slots);
+    db->consumed.resize(db->n_slots);
+    db->used.assign(db->n_slots, 0);
+    for (int i = 0; i < db->n_slots; ++i) {
+      hipError_t e = hipEventCreateWithFlags(&db->copied[i], hipEventDisableTiming);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&db->consumed[i], hipEventDisableTiming);
+      if (e != hipSuccess) {
+        // events created so far are leaked on this (never expected) path
+        delete db;
+        return hip_fail(e);
+      }
+    }
+  }
+  *out = db;
+  return AC_OK;
+}
+
+int32_t attncache_destroy_db(attncache_db* db) {
+  if (!db) return AC_ERR_NULL;
+  for (hipEvent_t ev : db->copied) (void)hipEventDestroy(ev);
+  for (hipEvent_t ev : db->consumed) (void)hipEventDestroy(ev);
+  delete db;
+  return AC_OK;
+}
+
+int32_t attncache_search(const attncache_db* db, const void* q, int32_t B, int32_t k,
+                         float threshold, int32_t* idx, float* score, int32_t* hit, void* ws,
+                         size_t ws_bytes, void* stream) {
+  if (!db) return AC_ERR_NULL;
+  if (B < 0) return AC_ERR_SHAPE;
+  if (k < 1 || k > AC_MAX_K || k > db->d.n_emb) return AC_ERR_K_RANGE;
+  if (B == 0) return AC_OK;
+  if (!q || !idx || !score || !hit || !ws) return AC_ERR_NULL;
+  if (!aligned16(q) || !aligned16(ws)) return AC_ERR_ALIGN;
+  const size_t need = ac::search_workspace_bytes(db->d.n_emb, db->d.emb_dim, B, k,
+                                                 db->d.emb_dtype == AC_F16);
+  if (ws_bytes < need) return AC_ERR_WORKSPACE;
+  ac::SearchLaunch p;
+  p.emb = db->emb; p.q = q; p.map_of = db->map_of;
+  p.N = db->d.n_emb; p.E = db->d.emb_dim; p.B = B; p.k = k;
+  p.is_f16 = db->d.emb_dtype == AC_F16; p.metric = db->d.metric;
+  p.threshold = threshold;
+  p.idx = idx; p.score = score; p.hit = hit;
+  p.ws = ws; p.ws_bytes = ws_bytes;
+  hipError_t e = ac::launch_search(p, reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AC_OK : hip_fail(e);
+}
+
+int32_t attncache_apply(const attncache_db* cdb, const int32_t* hit, const void* V, void* O,
+                        int32_t B, int32_t layer_begin, int32_t layer_count, void* stream_) {
+  attncache_db* db = const_cast<attncache_db*>(cdb);   // slot bookkeeping of the host path
+  if (!db) return AC_ERR_NULL;
+  const attncache_db_desc& d = db->d;
+  if (B < 0 || layer_begin < 0 || layer_count < 0 || layer_begin + layer_count > d.n_layers)
+    return AC_ERR_SHAPE;
+  if (B == 0 || layer_count == 0) return AC_OK;
+  if (!hit || !V || !O) return AC_ERR_NULL;
+  if (!aligned16(V) || !aligned16(O)) return AC_ERR_ALIGN;
+  hipStream_t stream = reinterpret_cast<hipStream_t>(stream_);
+
+  ac::ApplyLaunch p;
+  p.V = V; p.O = O; p.B = B; p.M = d.n_entries; p.L = d.n_layers;
+  p.layer_begin = layer_begin; p.Lc = layer_count;
+  p.Hq = d.n_q_heads; p.Hkv = d.n_kv_heads; p.S = d.seq_len; p.D = d.head_dim;
+  p.causal = d.causal; p.is_f32 = d.map_dtype == AC_F32;
+  p.n_list = 0;
+
+  if (!d.maps_on_host) {
+    p.maps = db->maps; p.hit = hit; p.fixed_entry = -1;
+    hipError_t e = ac::launch_apply(p, stream);
+    return e == hipSuccess ? AC_OK : hip_fail(e);
+  }
+
+  // Pinned-host maps: one host-to-device copy per distinct entry on the side stream, the
+  // products of all queries sharing that entry on the caller's stream as soon as the copy
+  // has landed.  Slots of the staging ring are recycled once their products are done.
+  for (int32_t b = 0; b < B; ++b)
+    if (hit[b] < -1 || hit[b] >= d.n_entries) return AC_ERR_INDEX;
+  std::vector<std::pair<int32_t, int32_t>> order;   // (entry, query), grouped by entry
+  order.reserve(B);
+  for (int32_t b = 0; b < B; ++b)
+    if (hit[b] >= 0) order.emplace_back(hit[b], b);
+  std::stable_sort(order.begin(), order.end(),
+                   [](const auto& x, const auto& y) { return x.first < y.first; });
+  const size_t layer_bytes = db->entry_bytes / d.n_layers;
+  const size_t copy_bytes = layer_bytes * layer_count;
+  size_t pos = 0;
+  while (pos < order.size()) {
+    const int32_t entry = order[pos].first;
+    size_t end = pos;
+    while (end < order.size() && order[end].first == entry) ++end;
+    const int slot = db->next_slot;
+    db->next_slot = (db->next_slot + 1) % db->n_slots;
+    unsigned char* dst = db->staging + (size_t)slot * db->entry_bytes;
+    const unsigned char* src = reinterpret_cast<const unsigned char*>(db->maps) +
+                               (size_t)entry * db->entry_bytes + (size_t)layer_begin * layer_bytes;
+    hipError_t e = hipSuccess;
+    if (db->used[slot]) e = hipStreamWaitEvent(db->side, db->consumed[slot], 0);
+    if (e == hipSuccess) e = hipMemcpyAsync(dst, src, copy_bytes, hipMemcpyHostToDevice, db->side);
+    if (e == hipSuccess) e = hipEventRecord(db->copied[slot], db->side);
+    if (e == hipSuccess) e = hipStreamWaitEvent(stream, db->copied[slot], 0);
+    if (e != hipSuccess) return hip_fail(e);
+    // the staged block holds layers [layer_begin, layer_begin + layer_count) only
+    p.maps = dst; p.hit = nullptr; p.fixed_entry = 0; p.L = layer_count; p.layer_begin = 0;
+    for (size_t q0 = pos; q0 < end; q0 += 32) {
+      p.n_list = (int32_t)std::min<size_t>(32, end - q0);
+      for (int i = 0; i < p.n_list; ++i) p.q_list[i] = order[q0 + i].second;
+      e = ac::launch_apply(p, stream);
+      if (e != hipSuccess) return hip_fail(e);
+    }
+    e = hipEventRecord(db->consumed[slot], stream);
+    if (e != hipSuccess) return hip_fail(e);
+    db->used[slot] = 1;
+    pos = end;
+  }
+  return AC_OK;
+}
+
+int32_t attention_exact(const void* Q, const void* K, const void* V, void* O,
+                        const int32_t* row_sel, int32_t B, int32_t Hq, int32_t Hkv, int32_t S,
+                        int32_t D, int32_t dtype, int32_t causal, float scale, void* stream) {
+  if (B < 0 || Hq < 1 || Hkv < 1 || S < 1 || D < 1 || Hq % Hkv != 0) return AC_ERR_SHAPE;
+  if (dtype == AC_BF16) {
+    if (S % 32 != 0 || (D != 64 && D != 128)) return AC_ERR_SHAPE;
+  } else if (dtype == AC_F32) {
+    if (D > 256) return AC_ERR_SHAPE;
+  } else {
+    return AC_ERR_DTYPE;
+  }
+  if (!(scale >= 0.f)) return AC_ERR_SHAPE;
+  if (B == 0) return AC_OK;
+  if (!Q || !K || !V || !O) return AC_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return AC_ERR_ALIGN;
+  ac::ExactLaunch p;
+  p.Q = Q; p.K = K; p.V = V; p.O = O; p.row_sel = row_sel;
+  p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.S = S; p.D = D;
+  p.causal = causal != 0; p.is_f32 = dtype == AC_F32; p.scale = scale;
+  hipError_t e = ac::launch_exact(p, reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AC_OK : hip_fail(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,58 @@
+// Host-side launch descriptors shared by the C-ABI layer (api.hip) and the
+// kernel files.  Everything here is plain data; validation happens in api.hip
+// before a descriptor is filled.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ac {
+
+// Dynamic LDS above 64 KiB needs a per-kernel opt-in; done once per kernel and size.
+template <auto Kernel>
+inline hipError_t ensure_lds(size_t bytes) {
+  static size_t granted = 64 * 1024;
+  if (bytes <= granted) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) granted = bytes;
+  return e;
+}
+
+struct ApplyLaunch {
+  const void* maps;      // device: whole database, or a single staged entry (fixed_entry >= 0)
+  const int32_t* hit;    // device [B]; unused when fixed_entry >= 0
+  const void* V;
+  void* O;
+  int32_t B, M, L, layer_begin, Lc, Hq, Hkv, S, D;
+  int32_t causal, is_f32;
+  int32_t fixed_entry;   // -1: index through hit[]
+  int32_t n_list;        // queries in q_list (<= 32) when fixed_entry >= 0
+  int32_t q_list[32];
+};
+hipError_t launch_apply(const ApplyLaunch& p, hipStream_t stream);
+
+struct ExactLaunch {
+  const void *Q, *K, *V;
+  void* O;
+  const int32_t* row_sel;
+  int32_t B, Hq, Hkv, S, D, causal, is_f32;
+  float scale;
+};
+hipError_t launch_exact(const ExactLaunch& p, hipStream_t stream);
+
+struct SearchLaunch {
+  const void* emb;        // device [N][E]
+  const void* q;          // device [B][E]
+  const int32_t* map_of;  // device [N] or nullptr
+  int32_t N, E, B, k, is_f16, metric;
+  float threshold;
+  int32_t *idx, *hit;
+  float* score;
+  void* ws;
+  size_t ws_bytes;
+};
+size_t search_workspace_bytes(int32_t N, int32_t E, int32_t B, int32_t k, int32_t is_f16);
+hipError_t launch_search(const SearchLaunch& p, hipStream_t stream);
+
+}  // namespace ac

@@ -1,0 +1,402 @@
+// Algorithm 1, search and threshold steps: exact top-k similarity search of a
+// batch of query feature vectors against the whole feature-vector database,
+// then hit / miss routing.  (The paper uses an approximate graph index; this
+// is the exact search that index approximates.)
+//
+// Two phases.
+//  1. score + group maximum.  The database rows are split into contiguous
+//     groups (one workgroup each).  The N x B score matrix is never written:
+//     a workgroup forms its scores on the matrix cores (fp16 inputs, fp32
+//     accumulation) and keeps, per query, only the best (score, row) of the
+//     group under the order "higher score, then lower row".
+//  2. finalise.  k = 1: the best group maximum is the answer.  k > 1: every
+//     member of the exact top-k lies in one of the k groups with the best
+//     maxima (each such group holds at least one of the k best elements), so
+//     those k groups are re-scored row by row and the k best rows selected.
+// fp32 databases (and the L2 metric) use a vector-ALU phase 1 of the same shape.
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace ac {
+
+constexpr int kQPad = 8;            // fp16 elements of padding per staged query row
+constexpr int kValuRowsPerWg = 256;
+constexpr int kIdxNone = 0x7fffffff;
+
+struct SearchArgs {
+  const void* emb;
+  const void* q;
+  const int32_t* map_of;
+  int32_t N, E, B, k, metric;
+  int32_t q0, nq;          // query super-block handled by this launch (phase 1)
+  int32_t rows_per_wg, G;  // group size and count
+  float threshold;
+  float* part_s;           // [B][G]
+  int32_t* part_i;         // [B][G]
+  float* cand;             // [B][k * rows_per_wg] (k > 1 only)
+  int32_t* idx;
+  float* score;
+  int32_t* hit;
+};
+
+// (s1, i1) ranks before (s0, i0): higher score, or equal score and lower row.
+__device__ __forceinline__ bool ranks_before(float s1, int i1, float s0, int i0) {
+  return s1 > s0 || (s1 == s0 && i1 < i0);
+}
+
+// Best (score, row) over a workgroup; result valid in every thread.
+__device__ __forceinline__ void block_argmax(float& s, int& i, float* red_s, int* red_i) {
+  for (int off = 32; off > 0; off >>= 1) {
+    const float so = __shfl_xor(s, off);
+    const int io = __shfl_xor(i, off);
+    if (ranks_before(so, io, s, i)) { s = so; i = io; }
+  }
+  const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();   // red_* may still be read from a previous call
+  if ((threadIdx.x & 63) == 0) { red_s[wave] = s; red_i[wave] = i; }
+  __syncthreads();
+  s = red_s[0]; i = red_i[0];
+  for (int w = 1; w < nw; ++w)
+    if (ranks_before(red_s[w], red_i[w], s, i)) { s = red_s[w]; i = red_i[w]; }
+}
+
+// ---------------------------------------------------------------- phase 1, matrix cores
+template <int KSMAX, int NQB>
+__global__ __launch_bounds__(kThreads) void search_f16_kernel(const SearchArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int E = a.E, QS = E + kQPad;
+  f16_t* qs = reinterpret_cast<f16_t*>(smem);                                 // [32 NQB][QS]
+  float* red_s = reinterpret_cast<float*>(smem + (size_t)32 * NQB * QS * 2);  // [4][32 NQB]
+  int* red_i = reinterpret_cast<int*>(red_s + 4 * 32 * NQB);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int il = lane & 31, kh = lane >> 5;
+  const int nks = E >> 4;
+
+  // stage the query super-block, zero rows beyond nq
+  {
+    const int EQ = E >> 3;
+    const u32x4* src = reinterpret_cast<const u32x4*>(reinterpret_cast<const f16_t*>(a.q) +
+                                                      (size_t)a.q0 * E);
+    for (int p = tid; p < 32 * NQB * EQ; p += kThreads) {
+      const int r = p / EQ, c = p % EQ;
+      u32x4 w = {0u, 0u, 0u, 0u};
+      if (r < a.nq) w = src[(size_t)r * EQ + c];
+      *reinterpret_cast<u32x4*>(qs + r * QS + 8 * c) = w;
+    }
+  }
+  __syncthreads();
+
+  float best_s[NQB];
+  int best_i[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) { best_s[qb] = -INFINITY; best_i[qb] = kIdxNone; }
+
+  const int row_begin = blockIdx.x * a.rows_per_wg;
+  const int row_end = min(row_begin + a.rows_per_wg, a.N);
+  const f16_t* emb = reinterpret_cast<const f16_t*>(a.emb);
+  for (int rb = row_begin + 32 * wave; rb < row_end; rb += 128) {
+    // database operand: lane (il, kh) holds emb[rb + il][16 ks + 8 kh .. +8); rows past the
+    // end are clamped for the load and masked below
+    const int rowc = min(rb + il, a.N - 1);
+    const f16_t* erow = emb + (size_t)rowc * E + 8 * kh;
+    f16x8 e[KSMAX];
+#pragma unroll
+    for (int ks = 0; ks < KSMAX; ++ks)
+      if (ks < nks) e[ks] = *reinterpret_cast<const f16x8*>(erow + 16 * ks);
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      f32x16 acc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+      const f16_t* qrow = qs + (32 * qb + il) * QS + 8 * kh;
+#pragma unroll
+      for (int ks = 0; ks < KSMAX; ++ks)
+        if (ks < nks) acc = mfma_f16(e[ks], *reinterpret_cast<const f16x8*>(qrow + 16 * ks), acc);
+      // acc[v] = <emb[rb + mfma_row(v)], q[32 qb + il]>; rows ascend with v, so a strict
+      // comparison keeps the lowest row among equal scores
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = rb + mfma_row(v, kh);
+        const float s = r < a.N ? acc[v] : -INFINITY;
+        if (s > best_s[qb]) { best_s[qb] = s; best_i[qb] = r; }
+      }
+    }
+  }
+  // combine the two lane halves, then the four waves
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const float so = __shfl_xor(best_s[qb], 32);
+    const int io = __shfl_xor(best_i[qb], 32);
+    if (ranks_before(so, io, best_s[qb], best_i[qb])) { best_s[qb] = so; best_i[qb] = io; }
+    if (kh == 0) {
+      red_s[wave * 32 * NQB + 32 * qb + il] = best_s[qb];
+      red_i[wave * 32 * NQB + 32 * qb + il] = best_i[qb];
+    }
+  }
+  __syncthreads();
+  for (int t = tid; t < a.nq; t += kThreads) {
+    float s = red_s[t];
+    int i = red_i[t];
+    for (int w = 1; w < 4; ++w) {
+      const float so = red_s[w * 32 * NQB + t];
+      const int io = red_i[w * 32 * NQB + t];
+      if (ranks_before(so, io, s, i)) { s = so; i = io; }
+    }
+    a.part_s[(size_t)(a.q0 + t) * a.G + blockIdx.x] = s;
+    a.part_i[(size_t)(a.q0 + t) * a.G + blockIdx.x] = i;
+  }
+}
+
+// ------------------------------------------------------------- vector-ALU scoring
+template <typename T>
+__device__ __forceinline__ float load_as_float(const T* p) { return (float)(*p); }
+
+// score of one database row against the query staged in LDS as fp32
+template <typename T>
+__device__ __forceinline__ float row_score(const T* __restrict__ row, const float* __restrict__ qf,
+                                           int E, int metric) {
+  float acc = 0.f;
+  if (metric == 0) {
+    for (int e = 0; e < E; ++e) acc = fmaf(qf[e], load_as_float(row + e), acc);
+  } else {
+    for (int e = 0; e < E; ++e) {
+      const float d = qf[e] - load_as_float(row + e);
+      acc = fmaf(-d, d, acc);
+    }
+  }
+  return acc;
+}
+
+// phase 1 on the vector ALUs: grid (G, B); one thread per database row.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void search_valu_kernel(const SearchArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float* qf = reinterpret_cast<float*>(smem);   // [E]
+  __shared__ float red_s[4];
+  __shared__ int red_i[4];
+  const int b = blockIdx.y, gidx = blockIdx.x;
+  const T* q = reinterpret_cast<const T*>(a.q) + (size_t)b * a.E;
+  for (int e = threadIdx.x; e < a.E; e += kThreads) qf[e] = load_as_float(q + e);
+  __syncthreads();
+  const int r = gidx * a.rows_per_wg + threadIdx.x;
+  float s = -INFINITY;
+  int i = kIdxNone;
+  if (threadIdx.x < a.rows_per_wg && r < a.N) {
+    s = row_score(reinterpret_cast<const T*>(a.emb) + (size_t)r * a.E, qf, a.E, a.metric);
+    i = r;
+  }
+  block_argmax(s, i, red_s, red_i);
+  if (threadIdx.x == 0) {
+    a.part_s[(size_t)b * a.G + gidx] = s;
+    a.part_i[(size_t)b * a.G + gidx] = i;
+  }
+}
+
+// ------------------------------------------------------------------- phase 2
+__device__ __forceinline__ void write_hit(const SearchArgs& a, int b, float s0, int i0) {
+  float sim = s0;
+  if (a.metric == 1) sim = 1.0f - sqrtf(-s0);
+  int entry = a.map_of ? a.map_of[i0] : i0;
+  a.hit[b] = (sim >= a.threshold) ? entry : -1;
+}
+
+// k = 1: best of the group maxima.
+__global__ __launch_bounds__(kThreads) void finalize_top1_kernel(const SearchArgs a) {
+  __shared__ float red_s[4];
+  __shared__ int red_i[4];
+  const int b = blockIdx.x;
+  float s = -INFINITY;
+  int i = kIdxNone;
+  for (int gi = threadIdx.x; gi < a.G; gi += kThreads) {
+    const float so = a.part_s[(size_t)b * a.G + gi];
+    const int io = a.part_i[(size_t)b * a.G + gi];
+    if (ranks_before(so, io, s, i)) { s = so; i = io; }
+  }
+  block_argmax(s, i, red_s, red_i);
+  if (threadIdx.x == 0) {
+    a.idx[b] = i;
+    a.score[b] = s;
+    write_hit(a, b, s, i);
+  }
+}
+
+// k > 1: pick the k best groups, re-score their rows, pick the k best rows.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void finalize_topk_kernel(const SearchArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float* qf = reinterpret_cast<float*>(smem);          // [E]
+  int* sel = reinterpret_cast<int*>(qf + a.E);         // [k] selected groups
+  __shared__ float red_s[4];
+  __shared__ int red_i[4];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int rpw = a.rows_per_wg;
+  const T* q = reinterpret_cast<const T*>(a.q) + (size_t)b * a.E;
+  for (int e = tid; e < a.E; e += kThreads) qf[e] = load_as_float(q + e);
+
+  // 1. the min(k, G) groups with the best maxima, in rank order
+  const int ng = min(a.k, a.G);
+  float last_s = INFINITY;
+  int last_i = -1;
+  for (int r = 0; r < ng; ++r) {
+    float s = -INFINITY;
+    int i = kIdxNone;
+    for (int gi = tid; gi < a.G; gi += kThreads) {
+      const float so = a.part_s[(size_t)b * a.G + gi];
+      const int io = a.part_i[(size_t)b * a.G + gi];
+      // only groups ranked strictly after the previous pick
+      if (ranks_before(last_s, last_i, so, io) && ranks_before(so, io, s, i)) { s = so; i = io; }
+    }
+    block_argmax(s, i, red_s, red_i);
+    if (tid == 0) sel[r] = (i == kIdxNone) ? -1 : i / rpw;
+    last_s = s; last_i = i;
+  }
+  __syncthreads();
+
+  // 2. re-score every row of the selected groups
+  float* cand = a.cand + (size_t)b * a.k * rpw;
+  for (int slot = tid; slot < ng * rpw; slot += kThreads) {
+    const int gsel = sel[slot / rpw];
+    const int r = gsel * rpw + slot % rpw;
+    float s = -INFINITY;
+    if (gsel >= 0 && r < a.N)
+      s = row_score(reinterpret_cast<const T*>(a.emb) + (size_t)r * a.E, qf, a.E, a.metric);
+    cand[slot] = s;
+  }
+  __syncthreads();
+
+  // 3. the k best rows among the candidates, in rank order
+  last_s = INFINITY; last_i = -1;
+  for (int r = 0; r < a.k; ++r) {
+    float s = -INFINITY;
+    int i = kIdxNone;
+    for (int slot = tid; slot < ng * rpw; slot += kThreads) {
+      const int gsel = sel[slot / rpw];
+      const int row = gsel * rpw + slot % rpw;
+      if (gsel < 0 || row >= a.N) continue;
+      const float so = cand[slot];
+      if (ranks_before(last_s, last_i, so, row) && ranks_before(so, row, s, i)) { s = so; i = row; }
+    }
+    block_argmax(s, i, red_s, red_i);
+    if (tid == 0) {
+      a.idx[(size_t)b * a.k + r] = i;
+      a.score[(size_t)b * a.k + r] = s;
+      if (r == 0) write_hit(a, b, s, i);
+    }
+    last_s = s; last_i = i;
+  }
+}
+
+// ------------------------------------------------------------------- host side
+static void search_plan(int32_t N, int32_t is_mfma, int32_t* rows_per_wg, int32_t* G) {
+  int rpw;
+  if (is_mfma) {
+    // 128 rows per pass of a workgroup; more passes per workgroup for large databases so that
+    // the query tile staged in LDS is amortised, while keeping >= ~1000 workgroups
+    long c = ((long)N + 128L * 1024 - 1) / (128L * 1024);
+    if (c < 1) c = 1;
+    if (c > 8) c = 8;
+    rpw = 128 * (int)c;
+  } else {
+    rpw = kValuRowsPerWg;
+  }
+  *rows_per_wg = rpw;
+  *G = (N + rpw - 1) / rpw;
+}
+
+static bool use_mfma(int32_t is_f16, int32_t metric, int32_t E) {
+  return is_f16 && metric == 0 && E % 16 == 0 && E <= 512;
+}
+
+size_t search_workspace_bytes(int32_t N, int32_t E, int32_t B, int32_t k, int32_t is_f16) {
+  // the plan depends on the metric only through the path choice; size for the larger of both
+  size_t need = 0;
+  for (int mfma = 0; mfma < 2; ++mfma) {
+    if (mfma && !use_mfma(is_f16, 0, E)) continue;
+    int32_t rpw, G;
+    search_plan(N, mfma, &rpw, &G);
+    size_t bytes = (size_t)B * G * 8;
+    bytes = (bytes + 255) / 256 * 256;
+    if (k > 1) bytes += (size_t)B * k * rpw * 4;
+    if (bytes > need) need = bytes;
+  }
+  return need + 256;
+}
+
+template <int KSMAX, int NQB>
+static hipError_t launch_f16_one(const SearchArgs& a, dim3 grid, size_t lds, hipStream_t stream) {
+  hipError_t e = ensure_lds<&search_f16_kernel<KSMAX, NQB>>(lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((search_f16_kernel<KSMAX, NQB>), grid, dim3(kThreads), lds, stream, a);
+  return hipGetLastError();
+}
+
+template <int KSMAX>
+static hipError_t launch_f16_phase1(const SearchArgs& a, int nqb, dim3 grid, size_t lds,
+                                    hipStream_t stream) {
+  switch (nqb) {
+    case 1: return launch_f16_one<KSMAX, 1>(a, grid, lds, stream);
+    case 2: return launch_f16_one<KSMAX, 2>(a, grid, lds, stream);
+    case 4: return launch_f16_one<KSMAX, 4>(a, grid, lds, stream);
+    default: return launch_f16_one<KSMAX, 8>(a, grid, lds, stream);
+  }
+}
+
+static size_t f16_lds_bytes(int nqb, int E) {
+  return (size_t)32 * nqb * (E + kQPad) * 2 + (size_t)4 * 32 * nqb * 8;
+}
+
+hipError_t launch_search(const SearchLaunch& p, hipStream_t stream) {
+  if (p.B == 0) return hipSuccess;
+  SearchArgs a;
+  a.emb = p.emb; a.q = p.q; a.map_of = p.map_of;
+  a.N = p.N; a.E = p.E; a.B = p.B; a.k = p.k; a.metric = p.metric;
+  a.threshold = p.threshold;
+  a.idx = p.idx; a.score = p.score; a.hit = p.hit;
+  const bool mfma = use_mfma(p.is_f16, p.metric, p.E);
+  search_plan(p.N, mfma, &a.rows_per_wg, &a.G);
+  unsigned char* ws = reinterpret_cast<unsigned char*>(p.ws);
+  size_t part_bytes = ((size_t)p.B * a.G * 8 + 255) / 256 * 256;
+  a.part_s = reinterpret_cast<float*>(ws);
+  a.part_i = reinterpret_cast<int32_t*>(ws + (size_t)p.B * a.G * 4);
+  a.cand = reinterpret_cast<float*>(ws + part_bytes);
+  a.q0 = 0; a.nq = p.B;
+
+  if (mfma) {
+    // query super-blocks of 32 * nqb queries; the staged tile must fit in LDS
+    const int ksmax = p.E <= 128 ? 8 : (p.E <= 256 ? 16 : 32);
+    int max_nqb = 8;
+    while (max_nqb > 1 && f16_lds_bytes(max_nqb, p.E) > 150 * 1024) max_nqb >>= 1;
+    for (int q0 = 0; q0 < p.B; q0 += 32 * max_nqb) {
+      a.q0 = q0;
+      a.nq = p.B - q0 < 32 * max_nqb ? p.B - q0 : 32 * max_nqb;
+      int nqb = 1;
+      while (32 * nqb < a.nq) nqb <<= 1;
+      const size_t lds = f16_lds_bytes(nqb, p.E);
+      const dim3 grid((unsigned)a.G);
+      hipError_t e;
+      if (ksmax == 8) e = launch_f16_phase1<8>(a, nqb, grid, lds, stream);
+      else if (ksmax == 16) e = launch_f16_phase1<16>(a, nqb, grid, lds, stream);
+      else e = launch_f16_phase1<32>(a, nqb, grid, lds, stream);
+      if (e != hipSuccess) return e;
+    }
+  } else {
+    const dim3 grid((unsigned)a.G, (unsigned)p.B);
+    const size_t lds = (size_t)p.E * 4;
+    if (p.is_f16) hipLaunchKernelGGL((search_valu_kernel<f16_t>), grid, dim3(kThreads), lds, stream, a);
+    else hipLaunchKernelGGL((search_valu_kernel<float>), grid, dim3(kThreads), lds, stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+
+  if (p.k == 1) {
+    hipLaunchKernelGGL(finalize_top1_kernel, dim3((unsigned)p.B), dim3(kThreads), 0, stream, a);
+  } else {
+    const size_t lds = (size_t)p.E * 4 + (size_t)p.k * 4;
+    if (p.is_f16) hipLaunchKernelGGL((finalize_topk_kernel<f16_t>), dim3((unsigned)p.B), dim3(kThreads), lds, stream, a);
+    else hipLaunchKernelGGL((finalize_topk_kernel<float>), dim3((unsigned)p.B), dim3(kThreads), lds, stream, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace ac

@@ -1,0 +1,295 @@
+"""GPU parity, small cases: the HIP library (through the C ABI) against the CPU oracle,
+element by element, on seeded inputs whose sizes span several tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ac():
+    assert torch.cuda.is_available(), "GPU tests need a GPU (no CPU fallback exists)"
+    from paper_2510_25979_amd import binding
+    binding.lib()
+    return binding
+
+
+def _gen(seed):
+    return torch.Generator(device="cpu").manual_seed(seed)
+
+
+def _maps(M, L, H, S, dtype, causal, seed):
+    logits = torch.randn(M, L, H, S, S, generator=_gen(seed))
+    if causal:
+        logits.masked_fill_(torch.ones(S, S, dtype=torch.bool).triu_(1), float("-inf"))
+    return torch.softmax(logits, -1).to(dtype)
+
+
+# ------------------------------------------------------------------------- apply
+
+APPLY_CASES = [
+    # B, M, L, Hq, Hkv, S, D, causal, layer_begin, Lc, dtype
+    (4, 16, 1, 2, 2, 32, 64, True, 0, 1, torch.float32),      # the tiny fp32 workload's shape
+    (3, 5, 2, 4, 2, 45, 24, False, 1, 1, torch.float32),      # odd sizes on the vector-ALU path
+    (5, 7, 3, 4, 4, 128, 64, True, 0, 3, torch.bfloat16),     # 1B-shaped heads
+    (4, 6, 2, 8, 2, 128, 128, True, 1, 1, torch.bfloat16),    # 8B-shaped heads (4 share a V)
+    (3, 4, 1, 2, 2, 96, 64, True, 0, 1, torch.bfloat16),      # one ragged block of rows
+    (2, 3, 2, 4, 1, 288, 128, True, 0, 2, torch.bfloat16),    # three row blocks, ragged last
+    (2, 3, 1, 2, 2, 160, 64, False, 0, 1, torch.bfloat16),    # dense maps
+    (2, 3, 1, 4, 2, 32, 128, False, 0, 1, torch.bfloat16),    # a single 32-row block
+    (9, 4, 1, 3, 3, 64, 64, True, 0, 1, torch.bfloat16),      # tile count not a multiple of 8
+]
+
+
+@pytest.mark.parametrize("case", APPLY_CASES, ids=lambda c: "B%d-M%d-L%d-H%d/%d-S%d-D%d-%s-%d+%d-%s" % (
+    c[0], c[1], c[2], c[3], c[4], c[5], c[6], "causal" if c[7] else "dense", c[8], c[9],
+    str(c[10]).split(".")[-1]))
+def test_apply_matches_oracle(ac, oracle_mod, case):
+    B, M, L, Hq, Hkv, S, D, causal, lb, Lc, dt = case
+    maps = _maps(M, L, Hq, S, dt, causal, 100 + S + D)
+    V = torch.randn(B, Lc, Hkv, S, D, generator=_gen(200 + S)).to(dt)
+    hit = torch.randint(0, M, (B,), generator=_gen(300 + B), dtype=torch.int32)
+    if B > 2:
+        hit[1] = -1                      # a miss: its output rows must stay untouched
+    emb = torch.zeros(M, 16, dtype=torch.float32)
+    db = ac.attncache_build_db(emb.cuda(), maps.cuda(), n_kv_heads=Hkv, head_dim=D, causal=causal)
+    O = torch.full((B, Lc, Hq, S, D), 7.0, dtype=dt, device="cuda")
+    ac.attncache_apply(db, hit.cuda(), V.cuda(), O, layer_begin=lb, layer_count=Lc)
+    torch.cuda.synchronize()
+    ref = oracle_mod.apply(parity.to_np(maps), hit.numpy(), parity.to_np(V), layer_begin=lb,
+                           out=np.full((B, Lc, Hq, S, D), 7.0))
+    err = parity.max_abs_err(O, ref)
+    assert err <= parity.TOL[dt], err
+    if B > 2:
+        assert (O[1] == 7.0).all()
+    db.close()
+
+
+def test_apply_identity_map_returns_v_bit_exactly(ac):
+    S, D = 128, 64
+    maps = torch.eye(S).expand(2, 1, 2, S, S).contiguous().to(torch.bfloat16)
+    V = torch.randn(3, 1, 2, S, D, generator=_gen(1)).to(torch.bfloat16)
+    db = ac.attncache_build_db(torch.zeros(2, 16).cuda(), maps.cuda(), n_kv_heads=2, head_dim=D)
+    O = torch.zeros(3, 1, 2, S, D, dtype=torch.bfloat16, device="cuda")
+    ac.attncache_apply(db, torch.tensor([0, 1, 0], dtype=torch.int32).cuda(), V.cuda(), O)
+    assert torch.equal(O.cpu(), V)
+
+
+def test_apply_out_of_range_hit_is_a_miss_on_device(ac):
+    S, D = 32, 64
+    maps = _maps(2, 1, 2, S, torch.bfloat16, True, 5)
+    db = ac.attncache_build_db(torch.zeros(2, 16).cuda(), maps.cuda(), n_kv_heads=2, head_dim=D)
+    V = torch.randn(2, 1, 2, S, D, generator=_gen(2)).to(torch.bfloat16).cuda()
+    O = torch.full((2, 1, 2, S, D), 3.0, dtype=torch.bfloat16, device="cuda")
+    ac.attncache_apply(db, torch.tensor([2, -5], dtype=torch.int32).cuda(), V, O)
+    assert (O == 3.0).all()
+    ac.attncache_apply(db, torch.zeros(0, dtype=torch.int32).cuda(), V[:0], O[:0])   # B = 0
+
+
+# ------------------------------------------------------------------------- exact
+
+EXACT_CASES = [
+    # B, Hq, Hkv, S, D, causal, scale, dtype
+    (4, 2, 2, 32, 64, True, 0.0, torch.float32),
+    (2, 4, 2, 45, 24, False, 0.3, torch.float32),
+    (3, 4, 4, 128, 64, True, 0.0, torch.bfloat16),
+    (3, 8, 2, 128, 128, True, 0.0, torch.bfloat16),
+    (2, 2, 2, 96, 64, True, 0.0, torch.bfloat16),
+    (2, 4, 1, 288, 128, True, 0.0, torch.bfloat16),
+    (2, 2, 2, 160, 64, False, 0.2, torch.bfloat16),
+    (1, 3, 3, 32, 128, False, 0.0, torch.bfloat16),
+    (9, 3, 1, 416, 64, True, 0.0, torch.bfloat16),
+]
+
+
+@pytest.mark.parametrize("case", EXACT_CASES, ids=lambda c: "B%d-H%d/%d-S%d-D%d-%s-%s" % (
+    c[0], c[1], c[2], c[3], c[4], "causal" if c[5] else "dense", str(c[7]).split(".")[-1]))
+def test_exact_matches_oracle(ac, oracle_mod, case):
+    B, Hq, Hkv, S, D, causal, scale, dt = case
+    g = _gen(400 + S + D)
+    Q = torch.randn(B, Hq, S, D, generator=g).to(dt)
+    K = torch.randn(B, Hkv, S, D, generator=g).to(dt)
+    V = torch.randn(B, Hkv, S, D, generator=g).to(dt)
+    row_sel = None
+    if B > 2:
+        row_sel = torch.full((B,), -1, dtype=torch.int32)
+        row_sel[1] = 4                   # served by the reuse branch: must be skipped
+    O = torch.full((B, Hq, S, D), 7.0, dtype=dt, device="cuda")
+    ac.attention_exact(Q.cuda(), K.cuda(), V.cuda(), O, causal=causal, scale=scale,
+                       row_sel=None if row_sel is None else row_sel.cuda())
+    torch.cuda.synchronize()
+    ref = oracle_mod.attention_exact(parity.to_np(Q), parity.to_np(K), parity.to_np(V), causal=causal,
+                                     scale=scale, row_sel=None if row_sel is None else row_sel.numpy(),
+                                     out=np.full((B, Hq, S, D), 7.0))
+    err = parity.max_abs_err(O, ref)
+    assert err <= parity.TOL[dt], err
+    if row_sel is not None:
+        assert (O[1] == 7.0).all()
+
+
+def test_exact_large_logits_stay_finite(ac, oracle_mod):
+    # peaked softmax: logits of magnitude ~60 must not overflow the online rescaling
+    B, H, S, D = 1, 2, 256, 64
+    g = _gen(7)
+    Q = (torch.randn(B, H, S, D, generator=g) * 6).to(torch.bfloat16)
+    K = (torch.randn(B, H, S, D, generator=g) * 6).to(torch.bfloat16)
+    V = torch.randn(B, H, S, D, generator=g).to(torch.bfloat16)
+    O = torch.empty(B, H, S, D, dtype=torch.bfloat16, device="cuda")
+    ac.attention_exact(Q.cuda(), K.cuda(), V.cuda(), O)
+    ref = oracle_mod.attention_exact(parity.to_np(Q), parity.to_np(K), parity.to_np(V))
+    assert parity.max_abs_err(O, ref) <= 2e-2
+
+
+def test_reusing_own_map_reproduces_exact_attention_on_gpu(ac, oracle_mod):
+    # maps computed (by the oracle) from the same Q, K and stored in bf16: the reuse branch
+    # must agree with the recompute branch
+    B, Hq, Hkv, S, D = 3, 4, 2, 128, 64
+    g = _gen(8)
+    Q = torch.randn(B, Hq, S, D, generator=g).to(torch.bfloat16)
+    K = torch.randn(B, Hkv, S, D, generator=g).to(torch.bfloat16)
+    V = torch.randn(B, Hkv, S, D, generator=g).to(torch.bfloat16)
+    _, P = oracle_mod.attention_exact(parity.to_np(Q), parity.to_np(K), parity.to_np(V), return_map=True)
+    maps = torch.from_numpy(oracle_mod.round_maps(P, oracle_mod.ROUND_BF16)).to(torch.bfloat16)
+    maps = maps.reshape(B, 1, Hq, S, S).contiguous()
+    db = ac.attncache_build_db(torch.zeros(B, 16).cuda(), maps.cuda(), n_kv_heads=Hkv, head_dim=D)
+    O_reuse = torch.empty(B, 1, Hq, S, D, dtype=torch.bfloat16, device="cuda")
+    ac.attncache_apply(db, torch.arange(B, dtype=torch.int32).cuda(), V.reshape(B, 1, Hkv, S, D).cuda(), O_reuse)
+    O_exact = torch.empty(B, Hq, S, D, dtype=torch.bfloat16, device="cuda")
+    ac.attention_exact(Q.cuda(), K.cuda(), V.cuda(), O_exact)
+    assert (O_reuse[:, 0].float() - O_exact.float()).abs().max().item() <= 4e-2
+    ref = oracle_mod.attention_exact(parity.to_np(Q), parity.to_np(K), parity.to_np(V))
+    assert parity.max_abs_err(O_exact, ref) <= 2e-2
+    assert parity.max_abs_err(O_reuse[:, 0].contiguous(), ref) <= 2e-2
+
+
+# ------------------------------------------------------------------------ search
+
+SEARCH_CASES = [
+    # N, E, B, k, dtype, metric, normalise
+    (1024, 128, 4, 1, torch.float32, "ip", False),      # the tiny workload
+    (1024, 128, 4, 3, torch.float32, "l2", False),
+    (777, 40, 5, 4, torch.float32, "ip", False),
+    (1000, 256, 64, 1, torch.float16, "ip", True),
+    (10000, 256, 64, 1, torch.float16, "ip", True),     # the 1B-shaped workload's index
+    (4097, 256, 100, 1, torch.float16, "ip", True),     # ragged rows and queries
+    (1024, 512, 16, 4, torch.float16, "ip", True),      # the long-sequence workload's index
+    (5000, 128, 300, 1, torch.float16, "ip", True),     # more than one query super-block
+    (77, 48, 3, 64, torch.float16, "ip", False),        # k = AC_MAX_K > rows per group
+    (3000, 256, 33, 8, torch.float16, "ip", True),
+    (600, 40, 7, 2, torch.float16, "ip", False),        # E % 16 != 0: vector-ALU path on fp16
+    (900, 64, 6, 2, torch.float16, "l2", False),
+    (140000, 64, 40, 4, torch.float16, "ip", True),     # several row passes per workgroup
+]
+
+
+def _run_search(ac, emb, q, k, theta, metric, map_of=None):
+    M = emb.shape[0] if map_of is None else int(map_of.max()) + 1
+    maps = torch.zeros(M, 1, 1, 32, 32, dtype=torch.float32)
+    db = ac.attncache_build_db(emb.cuda(), maps.cuda(), n_kv_heads=1, head_dim=8, metric=metric,
+                               map_of=None if map_of is None else map_of.cuda())
+    B = q.shape[0]
+    ws = torch.empty(ac.attncache_workspace_bytes(db.desc, B, k), dtype=torch.uint8, device="cuda")
+    idx = torch.full((B, k), -7, dtype=torch.int32, device="cuda")
+    score = torch.zeros(B, k, dtype=torch.float32, device="cuda")
+    hit = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    ac.attncache_search(db, q.cuda(), k, theta, idx, score, hit, ws)
+    torch.cuda.synchronize()
+    db.close()
+    return idx, score, hit
+
+
+@pytest.mark.parametrize("case", SEARCH_CASES, ids=lambda c: "N%d-E%d-B%d-k%d-%s-%s" % (
+    c[0], c[1], c[2], c[3], str(c[4]).split(".")[-1], c[5]))
+def test_search_matches_oracle(ac, oracle_mod, case):
+    N, E, B, k, dt, metric, normalise = case
+    g = _gen(500 + N + E)
+    raw = torch.randn(N, E, generator=g)
+    emb = (raw / raw.norm(dim=-1, keepdim=True) if normalise else raw).to(dt)
+    rows = torch.randint(0, N, (B,), generator=g)
+    qf = raw[rows] + 0.1 * torch.randn(B, E, generator=g)
+    qf[::3] = torch.randn(qf[::3].shape, generator=g)          # every third query is a miss
+    q = (qf / qf.norm(dim=-1, keepdim=True) if normalise else qf).to(dt)
+    m = ac.AC_IP if metric == "ip" else ac.AC_L2
+    theta = 0.9 if (normalise and metric == "ip") else (0.0 if metric == "ip" else -1.0)
+    idx, score, hit = _run_search(ac, emb, q, k, theta, m)
+    exempt = parity.check_search(oracle_mod, q, emb, k, theta, m, None, idx, score, hit)
+    assert exempt <= max(1, B * k // 50), exempt
+
+
+def test_search_ties_take_the_lowest_index(ac, oracle_mod):
+    g = _gen(9)
+    N, E = 2000, 256
+    emb = torch.randn(N, E, generator=g)
+    emb = (emb / emb.norm(dim=-1, keepdim=True)).to(torch.float16)
+    dup = [5, 130, 131, 1029, 1999]                  # identical rows across lanes, waves, groups
+    emb[dup] = emb[5].clone()
+    q = emb[[5, 700]].clone()
+    idx, score, hit = _run_search(ac, emb, q, 5, 0.5, ac.AC_IP)
+    assert idx[0].tolist() == dup
+    assert len(set(score[0].tolist())) == 1
+    idx1, _, hit1 = _run_search(ac, emb, q, 1, 0.5, ac.AC_IP)
+    assert idx1[:, 0].tolist() == [5, 700] and hit1.tolist() == [5, 700]
+
+
+def test_search_map_of_and_threshold(ac, oracle_mod):
+    g = _gen(10)
+    N, E, M = 3000, 256, 100
+    raw = torch.randn(N, E, generator=g)
+    emb = (raw / raw.norm(dim=-1, keepdim=True)).to(torch.float16)
+    map_of = (torch.arange(N) % M).to(torch.int32)
+    rows = torch.tensor([2999, 100, 250, 7])
+    qf = raw[rows] + 0.1 * torch.randn(4, E, generator=g)
+    qf[3] = torch.randn(E, generator=g)
+    q = (qf / qf.norm(dim=-1, keepdim=True)).to(torch.float16)
+    idx, score, hit = _run_search(ac, emb, q, 1, 0.9, ac.AC_IP, map_of=map_of)
+    assert idx[:3, 0].tolist() == rows[:3].tolist()
+    assert hit.tolist() == [2999 % M, 0, 250 % M, -1]
+    parity.check_search(oracle_mod, q, emb, 1, 0.9, ac.AC_IP, map_of, idx, score, hit)
+
+
+# ------------------------------------------------------------------ error paths
+
+def test_error_codes(ac):
+    emb = torch.zeros(64, 128, dtype=torch.float16, device="cuda")
+    maps = torch.zeros(64, 1, 2, 32, 32, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(ac.AttnCacheError) as e:       # maps promised on the device but on the host
+        d = ac.DbDesc(n_emb=64, emb_dim=128, emb_dtype=ac.AC_F16, metric=0, n_entries=64, n_layers=1,
+                      n_q_heads=2, n_kv_heads=2, head_dim=64, seq_len=32, map_dtype=ac.AC_BF16,
+                      causal=1, maps_on_host=0)
+        import ctypes
+        host = torch.zeros(64 * 2 * 32 * 32, dtype=torch.bfloat16)
+        h = ctypes.c_void_p()
+        ac._check(ac.lib().attncache_build_db(ctypes.byref(d), emb.data_ptr(), None, host.data_ptr(),
+                                              None, 0, None, ctypes.byref(h)), "attncache_build_db")
+    assert e.value.status == -9
+    db = ac.attncache_build_db(emb, maps, n_kv_heads=2, head_dim=64)
+    q = torch.zeros(4, 128, dtype=torch.float16, device="cuda")
+    idx = torch.zeros(4, 1, dtype=torch.int32, device="cuda")
+    score = torch.zeros(4, 1, device="cuda")
+    hit = torch.zeros(4, dtype=torch.int32, device="cuda")
+    tiny = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(ac.AttnCacheError) as e:
+        ac.attncache_search(db, q, 1, 0.5, idx, score, hit, tiny)
+    assert e.value.status == -6
+    ws = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(ac.AttnCacheError) as e:
+        ac.attncache_search(db, q, 65, 0.5, torch.zeros(4, 65, dtype=torch.int32, device="cuda"),
+                            torch.zeros(4, 65, device="cuda"), hit, ws)
+    assert e.value.status == -5
+    with pytest.raises(ac.AttnCacheError) as e:       # misaligned workspace
+        ac.attncache_search(db, q, 1, 0.5, idx, score, hit, ws[1:])
+    assert e.value.status == -4
+    V = torch.zeros(4, 1, 2, 32, 64, dtype=torch.bfloat16, device="cuda")
+    O = torch.zeros(4, 1, 2, 32, 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(ac.AttnCacheError) as e:       # layer range outside the database
+        ac.attncache_apply(db, hit, V, O, layer_begin=1, layer_count=1)
+    assert e.value.status == -2
+    with pytest.raises(ac.AttnCacheError) as e:       # S not a multiple of 32 on the bf16 path
+        x = torch.zeros(1, 1, 40, 64, dtype=torch.bfloat16, device="cuda")
+        ac.attention_exact(x, x, x, x.clone())
+    assert e.value.status == -2
+    ac.attncache_search(db, q, 1, 0.5, idx, score, hit, ws)   # the handle still works
+    torch.cuda.synchronize()
