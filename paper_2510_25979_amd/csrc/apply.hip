@@ -33,7 +33,7 @@ struct ApplyArgs {
 };
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(kThreads) void apply_bf16_kernel(const ApplyArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void apply_bf16_kernel(const ApplyArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* vt = reinterpret_cast<bf16_t*>(smem);                 // [D][kVtStride]
   bf16_t* ost_all = vt + D * kVtStride;                          // [4][32][D + 4]

@@ -31,7 +31,7 @@ struct ExactArgs {
 };
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(kThreads) void exact_bf16_kernel(const ExactArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void exact_bf16_kernel(const ExactArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int KS = D + kKPad;                       // staged K row stride (elements)
   bf16_t* ks_lds = reinterpret_cast<bf16_t*>(smem);  // [128][KS]; reused for the output tile
