@@ -56,7 +56,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=2, help="workload number 1..4 (default 2)")
     ap.add_argument("--entries", type=int, default=0, help="override the number of map entries")
+    ap.add_argument("--layout", choices=["packed", "dense"], default="packed",
+                    help="storage layout of the map database (default: packed)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch one plain 1 GiB device copy (a kernel of known HBM traffic "
+                         "against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -87,22 +92,33 @@ def main():
     emb, raw, map_of = synth.make_embeddings(w, dev)
     q, planted = synth.make_queries(w, raw, dev)
     del raw
-    log(f"workload {w.name}: allocating {w.n_entries} map entries of {w.entry_bytes / 2**20:.0f} MiB "
-        f"({w.n_entries * w.entry_bytes / 2**30:.1f} GiB)")
-    maps = torch.empty((w.n_entries, L, Hq, S, S), dtype=dt, device=dev)
+    packed = args.layout == "packed" and w.map_dtype == "bf16"
+    tile = ac.packed_tile_elems(S, w.causal) if packed else S * S
+    db_bytes = w.n_entries * L * Hq * tile * (2 if w.map_dtype == "bf16" else 4)
+    log(f"workload {w.name}: {w.n_entries} map entries, dense {w.entry_bytes / 2**20:.0f} MiB each; "
+        f"stored {'packed' if packed else 'dense'}: {db_bytes / 2**30:.1f} GiB")
+    maps = torch.empty((w.n_entries, L, Hq, tile) if packed else (w.n_entries, L, Hq, S, S),
+                       dtype=dt, device=dev)
     step_entries = max(1, (8 << 30) // w.entry_bytes)
+    scratch = torch.empty((min(step_entries, w.n_entries), L, Hq, S, S), dtype=dt, device=dev) \
+        if packed else None
     for e0 in range(0, w.n_entries, step_entries):
-        synth.fill_maps(w, maps[e0:e0 + step_entries], first_entry=e0)
+        e1 = min(w.n_entries, e0 + step_entries)
+        if packed:   # generate a dense slice, convert it into the database's storage layout
+            synth.fill_maps(w, scratch[:e1 - e0], first_entry=e0)
+            ac.attncache_pack_maps(scratch[:e1 - e0], maps[e0:e1], causal=w.causal)
+        else:
+            synth.fill_maps(w, maps[e0:e1], first_entry=e0)
         torch.cuda.synchronize()
-        log(f"  maps filled: {min(w.n_entries, e0 + step_entries)}/{w.n_entries} "
-            f"({time.time() - t0:.1f} s)")
+        log(f"  maps filled: {e1}/{w.n_entries} ({time.time() - t0:.1f} s)")
     Q, K, V = synth.make_qkv(w, dev)
     O = torch.zeros(B, L, Hq, S, D, dtype=dt, device=dev)
     O_exact = torch.zeros(B, L, Hq, S, D, dtype=dt, device=dev)
     torch.cuda.synchronize()
     log(f"inputs ready in {time.time() - t0:.1f} s")
 
-    db = ac.attncache_build_db(emb, maps, n_kv_heads=Hkv, head_dim=D, causal=w.causal, map_of=map_of)
+    db = ac.attncache_build_db(emb, maps, n_kv_heads=Hkv, head_dim=D, causal=w.causal, map_of=map_of,
+                               seq_len=S)
     ws = torch.empty(ac.attncache_workspace_bytes(db.desc, B, w.k), dtype=torch.uint8, device=dev)
     idx = torch.empty(B, w.k, dtype=torch.int32, device=dev)
     score = torch.empty(B, w.k, dtype=torch.float32, device=dev)
@@ -157,6 +173,14 @@ def main():
     torch.cuda.synchronize()
     exact_ms = sum(a.elapsed_time(b) for a, b in x_ev) / args.steps
 
+    if args.copy_probe:
+        probe_src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        probe_dst = torch.empty_like(probe_src)
+        torch.cuda.synchronize()
+        probe_dst.copy_(probe_src)          # reads 2^30 bytes, writes 2^30 bytes
+        torch.cuda.synchronize()
+        del probe_src, probe_dst
+
     tokens = B * S
     a_bytes = apply_algorithmic_bytes(w, n_hits)
     x_bytes = exact_algorithmic_bytes(w, B)
@@ -176,8 +200,10 @@ def main():
         "dtype": "bf16" if w.map_dtype == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "layers": L, "q_heads": Hq, "kv_heads": Hkv, "head_dim": D,
-                   "seq_len": S, "batch": B, "db_entries": w.n_entries, "db_gib": round(
-                       w.n_entries * w.entry_bytes / 2**30, 1), "emb": [w.n_emb, w.emb_dim],
+                   "seq_len": S, "batch": B, "db_entries": w.n_entries,
+                   "map_layout": "packed" if packed else "dense",
+                   "db_gib_dense": round(w.n_entries * w.entry_bytes / 2**30, 1),
+                   "db_gib_stored": round(db_bytes / 2**30, 1), "emb": [w.n_emb, w.emb_dim],
                    "k": w.k, "theta": w.theta, "hit_rate": n_hits / B},
         "breakdown_ms": {"search": search_ms, "apply": apply_ms, "exact_on_misses": miss_ms,
                          "exact_all_queries": exact_ms},
@@ -202,13 +228,23 @@ def main():
     if not args.no_cpu_baseline:
         import numpy as np
         import oracle
-        n_s = min(B, 4)
+        n_s = min(B, 16)
         hit_h = hit.cpu().numpy()
         sel = [b for b in range(B) if hit_h[b] >= 0][:n_s]
         t1 = time.perf_counter()
         oracle.search(q.float().cpu().numpy(), emb.float().cpu().numpy(), k=w.k, theta=w.theta)
         t_search = time.perf_counter() - t1
-        sub_maps = torch.stack([maps[int(hit_h[b])] for b in sel]).float().cpu().numpy()
+        dense_hits = torch.empty((len(sel), L, Hq, S, S), dtype=dt, device=dev)
+        for i, b in enumerate(sel):   # same seeded draw as the database slice holding this entry
+            e = int(hit_h[b])
+            e0 = e // step_entries * step_entries
+            n_slice = min(step_entries, w.n_entries - e0)
+            if packed:
+                synth.fill_maps(w, scratch[:n_slice], first_entry=e0)
+                dense_hits[i].copy_(scratch[e - e0])
+            else:
+                dense_hits[i].copy_(maps[e])
+        sub_maps = dense_hits.float().cpu().numpy()
         sub_V = V[sel].float().cpu().numpy()
         t1 = time.perf_counter()
         oracle.apply(sub_maps, np.arange(len(sel), dtype=np.int32), sub_V)

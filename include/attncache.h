@@ -55,6 +55,9 @@ extern "C" {
 #define AC_IP 0 /* similarity = inner product                               */
 #define AC_L2 1 /* score = -||q - e||^2, similarity = 1 - ||q - e||          */
 
+#define AC_LAYOUT_DENSE 0  /* each map is a row-major [S][S] matrix              */
+#define AC_LAYOUT_PACKED 1 /* block-packed, see attncache_pack_maps (bf16 only)   */
+
 #define AC_MAX_K 64
 
 /* ---- database ---------------------------------------------------------- */
@@ -69,8 +72,9 @@ extern "C" {
  * Supported: emb_dtype AC_F16 with metric AC_IP and emb_dim % 16 == 0
  * (matrix-core path), or emb_dtype AC_F32 with either metric and any emb_dim
  * (vector-ALU path).  map_dtype AC_BF16 with seq_len % 32 == 0 and head_dim
- * 64 or 128 (matrix-core path), or map_dtype AC_F32 with any seq_len and
- * head_dim <= 256 (vector-ALU path).  n_q_heads % n_kv_heads == 0.
+ * 64 or 128 (matrix-core path, either layout), or map_dtype AC_F32 with any
+ * seq_len and head_dim <= 256 (vector-ALU path, dense layout only).
+ * n_q_heads % n_kv_heads == 0.
  */
 typedef struct {
   int32_t n_emb;        /* N: feature vectors                                */
@@ -87,6 +91,7 @@ typedef struct {
   int32_t causal;       /* 1: every map is exactly 0 above the diagonal and
                            those blocks are never read; 0: dense maps        */
   int32_t maps_on_host; /* 0: maps is DEVICE memory; 1: pinned HOST memory   */
+  int32_t map_layout;   /* AC_LAYOUT_DENSE | AC_LAYOUT_PACKED                 */
 } attncache_db_desc;
 
 typedef struct attncache_db attncache_db; /* opaque, host-side */
@@ -99,20 +104,50 @@ int32_t attncache_workspace_bytes(const attncache_db_desc *desc,
                                   int32_t max_batch, int32_t k, size_t *out);
 
 /*
+ * Bytes of one map entry (all layers and heads of one database item) in the
+ * layout desc->map_layout.  Dense: L*Hq*S*S elements.  Packed causal:
+ * L*Hq*(S/32)*(S/32+1)*512 elements (20 KiB instead of 32 KiB per head at
+ * S = 128); packed non-causal: the same count as dense.
+ */
+int32_t attncache_map_entry_bytes(const attncache_db_desc *desc, size_t *out);
+
+/*
+ * Storage format conversion of the store step (Fig. 3, step 3): rewrite
+ * n_entries dense maps into the packed layout the reuse kernel reads fastest.
+ *
+ *   dense   DEVICE [n_entries][L][Hq][S][S] bf16.
+ *   packed  DEVICE, n_entries * attncache_map_entry_bytes(packed desc) bytes.
+ *
+ * Packed layout of one [S][S] map: rows are cut into blocks of 16, columns
+ * into blocks of 32.  Row block r keeps its first nc(r) column blocks, nc(r) =
+ * ceil((r+1)/2) for causal maps (everything above is zero by definition and is
+ * dropped), S/32 otherwise.  Blocks are stored row-block-major; inside a block
+ * (16 x 32 = 512 elements) element (i, 8q + e), q in 0..3, e in 0..7, sits at
+ * offset (16q + i)*8 + e, which is the operand order of the 16x16x32 matrix
+ * instruction.  desc->map_layout is ignored here (the result IS packed);
+ * desc->map_dtype must be AC_BF16.  Entries can be converted in slices, so
+ * the dense form never has to exist as a whole.
+ */
+int32_t attncache_pack_maps(const attncache_db_desc *desc, const void *dense,
+                            int32_t n_entries, void *packed, void *stream);
+
+/*
  * Store step of database building (Fig. 3, step 3): bind finished feature
  * vectors and attention maps into one searchable handle.
  *
  *   emb       DEVICE [N][E] of emb_dtype.
  *   map_of    DEVICE [N] int32 with values in [0, M), or NULL for the
  *             identity (requires N == M): map entry of each feature vector.
- *   maps      [M][L][Hq][S][S] of map_dtype; DEVICE, or pinned HOST memory
- *             (hipHostMalloc) when desc->maps_on_host.  Each row of each map
- *             sums to 1; with desc->causal the part above the diagonal is 0.
- *             One entry is one contiguous block (all layers of one item lie
- *             together, as the paper's layer-adjacent layout).
+ *   maps      M entries of attncache_map_entry_bytes() each, of map_dtype, in
+ *             the layout desc->map_layout (dense: [M][L][Hq][S][S]); DEVICE,
+ *             or pinned HOST memory (hipHostMalloc) when desc->maps_on_host.
+ *             Each row of each map sums to 1; with desc->causal the part
+ *             above the diagonal is 0.  One entry is one contiguous block (all
+ *             layers of one item lie together, as the paper's layer-adjacent
+ *             layout).
  *   staging   DEVICE ring buffer of staging_bytes, used only when
- *             maps_on_host; must hold at least two entries
- *             (2 * L*Hq*S*S*sizeof(map element)).  NULL / 0 otherwise.
+ *             maps_on_host; must hold at least two entries.  NULL / 0
+ *             otherwise.
  *   side_stream  hipStream_t on which host-to-device map copies are issued;
  *             used only when maps_on_host (must differ from the stream
  *             later passed to attncache_apply).

@@ -19,11 +19,13 @@ from . import build as _build
 
 AC_F32, AC_F16, AC_BF16 = 0, 1, 2
 AC_IP, AC_L2 = 0, 1
+AC_LAYOUT_DENSE, AC_LAYOUT_PACKED = 0, 1
 AC_MAX_K = 64
 
 _DTYPE_CODE = {torch.float32: AC_F32, torch.float16: AC_F16, torch.bfloat16: AC_BF16}
 
-SYMBOLS = ["attncache_workspace_bytes", "attncache_build_db", "attncache_destroy_db",
+SYMBOLS = ["attncache_workspace_bytes", "attncache_map_entry_bytes", "attncache_pack_maps",
+           "attncache_build_db", "attncache_destroy_db",
            "attncache_search", "attncache_apply", "attention_exact", "attncache_status_string",
            "attncache_last_hip_error", "attncache_version"]
 
@@ -39,7 +41,7 @@ class AttnCacheError(RuntimeError):
 class DbDesc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "n_emb", "emb_dim", "emb_dtype", "metric", "n_entries", "n_layers", "n_q_heads",
-        "n_kv_heads", "head_dim", "seq_len", "map_dtype", "causal", "maps_on_host")]
+        "n_kv_heads", "head_dim", "seq_len", "map_dtype", "causal", "maps_on_host", "map_layout")]
 
 
 _lib = None
@@ -61,6 +63,10 @@ def lib():
         i32, f32, vp, sz = ctypes.c_int32, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
         L.attncache_workspace_bytes.restype = i32
         L.attncache_workspace_bytes.argtypes = [ctypes.POINTER(DbDesc), i32, i32, ctypes.POINTER(sz)]
+        L.attncache_map_entry_bytes.restype = i32
+        L.attncache_map_entry_bytes.argtypes = [ctypes.POINTER(DbDesc), ctypes.POINTER(sz)]
+        L.attncache_pack_maps.restype = i32
+        L.attncache_pack_maps.argtypes = [ctypes.POINTER(DbDesc), vp, i32, vp, vp]
         L.attncache_build_db.restype = i32
         L.attncache_build_db.argtypes = [ctypes.POINTER(DbDesc), vp, vp, vp, vp, sz, vp,
                                          ctypes.POINTER(vp)]
@@ -132,14 +138,54 @@ def attncache_workspace_bytes(desc: DbDesc, max_batch: int, k: int) -> int:
     return int(out.value)
 
 
+def attncache_map_entry_bytes(desc: DbDesc) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().attncache_map_entry_bytes(ctypes.byref(desc), ctypes.byref(out)),
+           "attncache_map_entry_bytes")
+    return int(out.value)
+
+
+def packed_tile_elems(seq_len: int, causal: bool) -> int:
+    """Elements of one packed [S][S] map (what attncache_map_entry_bytes reports per head)."""
+    d = DbDesc(n_emb=1, emb_dim=8, emb_dtype=AC_F16, metric=AC_IP, n_entries=1, n_layers=1,
+               n_q_heads=1, n_kv_heads=1, head_dim=64, seq_len=seq_len, map_dtype=AC_BF16,
+               causal=int(causal), maps_on_host=0, map_layout=AC_LAYOUT_PACKED)
+    return attncache_map_entry_bytes(d) // 2
+
+
+def attncache_pack_maps(dense: torch.Tensor, packed: torch.Tensor, *, causal: bool = True,
+                        stream: Optional[torch.cuda.Stream] = None) -> None:
+    """dense [n,L,Hq,S,S] bf16 (cuda) -> packed [n,L,Hq,packed_tile_elems(S)] bf16 (cuda)."""
+    if dense.dim() != 5 or dense.shape[3] != dense.shape[4]:
+        raise ValueError("dense must be [n,L,Hq,S,S]")
+    n, L, Hq, S, _ = dense.shape
+    d = DbDesc(n_emb=1, emb_dim=8, emb_dtype=AC_F16, metric=AC_IP, n_entries=max(n, 1), n_layers=L,
+               n_q_heads=Hq, n_kv_heads=Hq, head_dim=64, seq_len=S, map_dtype=AC_BF16,
+               causal=int(causal), maps_on_host=0, map_layout=AC_LAYOUT_PACKED)
+    dp = _dev(dense, "dense", torch.bfloat16)
+    pp = _dev(packed, "packed", torch.bfloat16, (n, L, Hq, packed_tile_elems(S, causal)))
+    _check(lib().attncache_pack_maps(ctypes.byref(d), dp, n, pp, _stream(stream)),
+           "attncache_pack_maps")
+
+
 def attncache_build_db(emb: torch.Tensor, maps: torch.Tensor, *, n_kv_heads: int, head_dim: int,
                        metric: int = AC_IP, causal: bool = True,
                        map_of: Optional[torch.Tensor] = None,
                        staging: Optional[torch.Tensor] = None,
-                       side_stream: Optional[torch.cuda.Stream] = None) -> Database:
-    """emb [N,E] (cuda, f16/f32); maps [M,L,Hq,S,S] (cuda, or pinned host) bf16/f32."""
-    if emb.dim() != 2 or maps.dim() != 5 or maps.shape[3] != maps.shape[4]:
+                       side_stream: Optional[torch.cuda.Stream] = None,
+                       seq_len: Optional[int] = None) -> Database:
+    """emb [N,E] (cuda, f16/f32); maps (cuda, or pinned host) bf16/f32: dense [M,L,Hq,S,S], or
+    packed [M,L,Hq,packed_tile_elems(S)] with ``seq_len`` given."""
+    packed = maps.dim() == 4
+    if packed:
+        if seq_len is None or maps.shape[3] != packed_tile_elems(seq_len, causal):
+            raise ValueError("packed maps must be [M,L,Hq,packed_tile_elems(seq_len)]")
+    elif emb.dim() != 2 or maps.dim() != 5 or maps.shape[3] != maps.shape[4]:
         raise ValueError("emb must be [N,E] and maps [M,L,Hq,S,S]")
+    else:
+        if seq_len is not None and seq_len != maps.shape[3]:
+            raise ValueError("seq_len disagrees with the dense maps")
+        seq_len = maps.shape[3]
     on_host = not maps.is_cuda
     if on_host and not maps.is_pinned():
         raise ValueError("host-resident maps must be pinned memory")
@@ -150,8 +196,9 @@ def attncache_build_db(emb: torch.Tensor, maps: torch.Tensor, *, n_kv_heads: int
     d = DbDesc(n_emb=emb.shape[0], emb_dim=emb.shape[1], emb_dtype=_DTYPE_CODE[emb.dtype],
                metric=metric, n_entries=maps.shape[0], n_layers=maps.shape[1],
                n_q_heads=maps.shape[2], n_kv_heads=n_kv_heads, head_dim=head_dim,
-               seq_len=maps.shape[3], map_dtype=_DTYPE_CODE[maps.dtype], causal=int(causal),
-               maps_on_host=int(on_host))
+               seq_len=seq_len, map_dtype=_DTYPE_CODE[maps.dtype], causal=int(causal),
+               maps_on_host=int(on_host),
+               map_layout=AC_LAYOUT_PACKED if packed else AC_LAYOUT_DENSE)
     emb_p = _dev(emb, "emb")
     mo_p = None if map_of is None else _dev(map_of, "map_of", torch.int32, (emb.shape[0],))
     st_p, st_bytes, ss = None, 0, None

@@ -56,10 +56,19 @@ int32_t check_desc(const attncache_db_desc* d) {
     if (d->head_dim != 64 && d->head_dim != 128) return AC_ERR_SHAPE;
   } else if (d->map_dtype == AC_F32) {
     if (d->head_dim > 256) return AC_ERR_SHAPE;
+    if (d->map_layout != AC_LAYOUT_DENSE) return AC_ERR_DTYPE;
   } else {
     return AC_ERR_DTYPE;
   }
+  if (d->map_layout != AC_LAYOUT_DENSE && d->map_layout != AC_LAYOUT_PACKED) return AC_ERR_DTYPE;
   return AC_OK;
+}
+
+size_t entry_bytes_of(const attncache_db_desc* d) {
+  const size_t heads = (size_t)d->n_layers * d->n_q_heads;
+  if (d->map_layout == AC_LAYOUT_PACKED)
+    return heads * (size_t)ac::packed_blocks(d->seq_len, d->causal) * 512 * elt_size(d->map_dtype);
+  return heads * d->seq_len * d->seq_len * elt_size(d->map_dtype);
 }
 
 }  // namespace
@@ -114,6 +123,33 @@ int32_t attncache_workspace_bytes(const attncache_db_desc* desc, int32_t max_bat
   return AC_OK;
 }
 
+int32_t attncache_map_entry_bytes(const attncache_db_desc* desc, size_t* out) {
+  if (!out) return AC_ERR_NULL;
+  int32_t rc = check_desc(desc);
+  if (rc != AC_OK) return rc;
+  *out = entry_bytes_of(desc);
+  return AC_OK;
+}
+
+int32_t attncache_pack_maps(const attncache_db_desc* desc, const void* dense, int32_t n_entries,
+                            void* packed, void* stream) {
+  if (!desc) return AC_ERR_NULL;
+  attncache_db_desc d = *desc;
+  d.map_layout = AC_LAYOUT_PACKED;
+  int32_t rc = check_desc(&d);
+  if (rc != AC_OK) return rc;
+  if (d.map_dtype != AC_BF16) return AC_ERR_DTYPE;
+  if (n_entries < 0) return AC_ERR_SHAPE;
+  if (n_entries == 0) return AC_OK;
+  if (!dense || !packed) return AC_ERR_NULL;
+  if (!aligned16(dense) || !aligned16(packed)) return AC_ERR_ALIGN;
+  const int64_t tiles = (int64_t)n_entries * d.n_layers * d.n_q_heads;
+  if (tiles > 0x7fffffffLL) return AC_ERR_SHAPE;
+  hipError_t e = ac::launch_pack_maps(dense, packed, tiles, d.seq_len, d.causal != 0,
+                                      reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AC_OK : hip_fail(e);
+}
+
 int32_t attncache_build_db(const attncache_db_desc* desc, const void* emb, const int32_t* map_of,
                            const void* maps, void* staging, size_t staging_bytes,
                            void* side_stream, attncache_db** out) {
@@ -138,8 +174,7 @@ int32_t attncache_build_db(const attncache_db_desc* desc, const void* emb, const
   db->n_slots = 0;
   db->next_slot = 0;
   db->side = nullptr;
-  db->entry_bytes = (size_t)desc->n_layers * desc->n_q_heads * desc->seq_len * desc->seq_len *
-                    elt_size(desc->map_dtype);
+  db->entry_bytes = entry_bytes_of(desc);
   if (desc->maps_on_host) {
     if (!staging) { delete db; return AC_ERR_NULL; }
     if (!aligned16(staging)) { delete db; return AC_ERR_ALIGN; }
@@ -213,6 +248,7 @@ int32_t attncache_apply(const attncache_db* cdb, const int32_t* hit, const void*
   p.layer_begin = layer_begin; p.Lc = layer_count;
   p.Hq = d.n_q_heads; p.Hkv = d.n_kv_heads; p.S = d.seq_len; p.D = d.head_dim;
   p.causal = d.causal; p.is_f32 = d.map_dtype == AC_F32;
+  p.packed = d.map_layout == AC_LAYOUT_PACKED;
   p.n_list = 0;
 
   if (!d.maps_on_host) {

@@ -2,24 +2,35 @@
 // place from the database (the hit index selects the entry; nothing is
 // gathered or copied first).
 //
-// bf16 path (matrix cores).  One workgroup = one (query, layer, head group,
-// block of 128 map rows); a wave owns 32 map rows.  The product is formed
+// bf16 path (matrix cores, v_mfma_f32_16x16x32_bf16).  One workgroup = one
+// (query, layer, head group, block of 128 map rows).  The product is formed
 // transposed, O^T = V^T A^T, so that
-//   - the map operand (columns of A^T = rows of A) is eight consecutive bf16
-//     of one map row per lane: a plain 16-byte global load, no LDS;
+//   - the map operand is eight consecutive bf16 of one map row per lane: a
+//     plain 16-byte global load straight into the MFMA operand, no LDS;
 //   - the V operand comes from an LDS tile that was transposed while staging;
-//   - each lane ends up with runs of four consecutive d of one output row.
-// Causal maps are exactly zero above the diagonal, so a wave reads only the
-// column range [0, last row of its block]; nothing above is fetched.
-// HBM-bound: per (query, layer, head) the kernel moves about S(S+32) map
-// bytes... (bf16: 2 bytes each) plus V and O once.
+//   - each lane ends up with four consecutive d of one output row.
+// Causal maps are exactly zero above the diagonal: 16-row block r only needs
+// its first ceil((r+1)/2) blocks of 32 columns.  A wave owns row blocks w and
+// 7-w of the 128-row block, which gives every wave the same five column
+// blocks on the diagonal chunk (1+4, 1+4, 2+3, 2+3).
+//
+// Two storage layouts of a map [S][S]:
+//   dense   row-major, as computed;
+//   packed  only the needed 16 x 32 blocks, row-block-major, each block (1 KiB)
+//           stored in MFMA operand order: element (i, 8q+e) of the block at
+//           offset (16 q + i) * 8 + e.  A wave's load of one block is then one
+//           contiguous KiB, a tile is one contiguous run of 20 KiB (S = 128)
+//           instead of 32 KiB with holes, and no 128-byte line is fetched for
+//           only half of its bytes.
+// HBM-bound: per (query, layer, head) the kernel moves S(S+32) map bytes
+// (causal bf16), V once per head group and O once.
 #include "common.hpp"
 #include "launch.hpp"
 
 namespace ac {
 
 struct ApplyArgs {
-  const void* maps;     // [M][L][Hq][S][S] (device), or one staged entry
+  const void* maps;     // [M][L][Hq][tile] (device), or one staged entry
   const int32_t* hit;   // [B] device, or nullptr when q_list is used
   const void* V;
   void* O;
@@ -32,21 +43,30 @@ struct ApplyArgs {
   int32_t q_list[32];    // queries served by the staged entry
 };
 
-template <int D, bool CAUSAL>
-__global__ __launch_bounds__(kThreads, 2) void apply_bf16_kernel(const ApplyArgs a) {
+__device__ __forceinline__ f32x4 mfma16_bf16(u32x4 a, u32x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// PREFETCH: the map pieces of the next (head, chunk) step are requested before the products of
+// the current one, so a workgroup that walks several steps always has loads in flight.
+template <int D, bool CAUSAL, bool PACKED, bool PREFETCH>
+__global__ __launch_bounds__(kThreads, (D == 64 ? (PREFETCH ? 3 : 4) : 2))
+void apply_bf16_kernel(const ApplyArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* vt = reinterpret_cast<bf16_t*>(smem);                 // [D][kVtStride]
   bf16_t* ost_all = vt + D * kVtStride;                          // [4][32][D + 4]
+  constexpr int OS = D + 4;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int il = lane & 31, kh = lane >> 5;
+  const int i16 = lane & 15, kq = lane >> 4;
 
-  // Block id -> (tile, row block).  The eight row blocks... of one tile share V, and
-  // workgroups are handed to the 8 XCDs round-robin by id, so ids that differ
-  // by a multiple of 8 (same XCD, same L2) are given to one tile.
+  // Block id -> (tile, 128-row block R).  The row blocks of one tile share V, and workgroups
+  // are handed to the 8 XCDs round-robin by id, so ids that differ by a multiple of 8 (same
+  // XCD, same L2) are given to one tile.  Heaviest (last) row block first.
   const int bid = blockIdx.x;
   const int tile = (bid >> 3) / a.n_rblk * 8 + (bid & 7);
-  const int rblk = a.n_rblk - 1 - (bid >> 3) % a.n_rblk;   // heaviest row block first
+  const int R = a.n_rblk - 1 - (bid >> 3) % a.n_rblk;
   if (tile >= a.n_tiles) return;
   const int hgroups = a.Hq / a.heads_per_wg;
   const int hg = tile % hgroups;
@@ -66,71 +86,156 @@ __global__ __launch_bounds__(kThreads, 2) void apply_bf16_kernel(const ApplyArgs
   const int S = a.S, g = a.Hq / a.Hkv;
   const int h0 = hg * a.heads_per_wg;
   const int kvh = h0 / g;
+  const int n16 = S >> 4, n32 = S >> 5;
+  const size_t tile_elems = PACKED ? (size_t)packed_blocks(S, CAUSAL) * 512 : (size_t)S * S;
   const bf16_t* Vt_src = reinterpret_cast<const bf16_t*>(a.V) +
                          (((size_t)b * a.Lc + l) * a.Hkv + kvh) * (size_t)S * D;
-  const size_t layer_stride = (size_t)a.Hq * S * S;
   const bf16_t* A_layer = reinterpret_cast<const bf16_t*>(a.maps) +
-                          ((size_t)entry * a.L + (a.layer_begin + l)) * layer_stride;
+                          ((size_t)entry * a.L + (a.layer_begin + l)) * ((size_t)a.Hq * tile_elems);
 
-  const int r0 = rblk * kChunk + wave * kRowsPerWave;   // first map row of this wave
-  const bool active = r0 < S;
-  const int n_chunk = CAUSAL ? rblk + 1 : (S + kChunk - 1) / kChunk;
+  const int nloc = min(8, n16 - 8 * R);       // 16-row blocks present in this 128-row block
+  const int rA = wave, rB = 7 - wave;         // the two row blocks of this wave
+  const bool hasA = rA < nloc, hasB = rB < nloc;
+  const int n_chunk = CAUSAL ? R + 1 : (S + kChunk - 1) / kChunk;
 
+  // 16-byte operand piece of (16-row block r, 32-column block cb) for this lane
+  auto piece = [&](const bf16_t* At, int r, int cb) -> const u32x4* {
+    if (PACKED)
+      return reinterpret_cast<const u32x4*>(
+          At + (size_t)((CAUSAL ? packed_prefix(r) : r * n32) + cb) * 512 + lane * 8);
+    return reinterpret_cast<const u32x4*>(At + (size_t)(16 * r + i16) * S + 32 * cb + 8 * kq);
+  };
+  // column blocks (of the 128-column chunk c) that row blocks A and B need
+  auto steps = [&](int c, int& nA, int& nB) {
+    const int nk = min(kChunk, S - c * kChunk) >> 5;
+    const bool diag = CAUSAL && c == R;
+    nA = hasA ? (diag ? (rA >> 1) + 1 : nk) : 0;
+    nB = hasB ? (diag ? (rB >> 1) + 1 : nk) : 0;
+  };
+  auto issue = [&](const bf16_t* At, int c, u32x4 (&am)[8]) {
+    int nA, nB;
+    steps(c, nA, nB);
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+      if (t < nA + nB) {
+        const bool inA = t < nA;
+        am[t] = *piece(At, 8 * R + (inA ? rA : rB), 4 * c + (inA ? t : t - nA));
+      }
+  };
+
+  u32x4 am[8], am_next[8];
+  if (PREFETCH) issue(A_layer + (size_t)h0 * tile_elems, 0, am_next);
   for (int hl = 0; hl < a.heads_per_wg; ++hl) {
     const int h = h0 + hl;
-    const bf16_t* Arow = A_layer + (size_t)h * S * S + (size_t)(r0 + il) * S + 8 * kh;
-    f32x16 acc[D / 32];
+    const bf16_t* At = A_layer + (size_t)h * tile_elems;
+    f32x4 accA[D / 16], accB[D / 16];
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
-
+    for (int db = 0; db < D / 16; ++db) {
+      accA[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+      accB[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
     for (int c = 0; c < n_chunk; ++c) {
-      const int j0 = c * kChunk;
-      const int nj = min(kChunk, S - j0);
-      // columns this wave needs from the chunk (multiple of 32; causal: up to its last row)
-      int ncol = active ? nj : 0;
-      if (CAUSAL && active) ncol = min(nj, r0 + kRowsPerWave - j0);
-      const int nks = ncol >> 4;
-
-      // 1. issue the map loads first: they stay in flight while V is staged
-      bf16x8 am[8];
+      int nA, nB;
+      steps(c, nA, nB);
+      // 1. map pieces: requested first, so that they are in flight while V is staged
+      if (PREFETCH) {
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks)
-        if (ks < nks) am[ks] = *reinterpret_cast<const bf16x8*>(Arow + j0 + 16 * ks);
-
-      // 2. stage V^T for this chunk (once per workgroup; shared by its heads)
+        for (int t = 0; t < 8; ++t) am[t] = am_next[t];
+      } else {
+        issue(At, c, am);
+      }
+      // 2. V^T of this chunk into LDS (once per workgroup; shared by its heads)
       if (hl == 0 || n_chunk > 1) {
         if (c > 0 || hl > 0) __syncthreads();
-        stage_v_transposed<D>(Vt_src + (size_t)j0 * D, nj, vt, tid);
+        stage_v_transposed<D>(Vt_src + (size_t)c * kChunk * D, min(kChunk, S - c * kChunk), vt, tid);
         __syncthreads();
       }
-
+      if (PREFETCH) {
+        if (c + 1 < n_chunk) issue(At, c + 1, am_next);
+        else if (hl + 1 < a.heads_per_wg) issue(At + tile_elems, 0, am_next);
+      }
       // 3. O^T[d][i] += sum_j V^T[d][j] A^T[j][i]
+      auto vop = [&](int db, int ks) {
+        const u32x2* src = reinterpret_cast<const u32x2*>(vt + (16 * db + i16) * kVtStride +
+                                                          32 * ks + 8 * kq);
+        u32x2 lo = src[0], hi = src[1];
+        return u32x4{lo.x, lo.y, hi.x, hi.y};
+      };
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        if (ks < nks) {
+      for (int t = 0; t < 8; ++t) {
+        if (t < nA) {
 #pragma unroll
-          for (int db = 0; db < D / 32; ++db) {
-            const u32x2* src =
-                reinterpret_cast<const u32x2*>(vt + (32 * db + il) * kVtStride + 16 * ks + 8 * kh);
-            u32x2 lo = src[0], hi = src[1];
-            u32x4 w = {lo.x, lo.y, hi.x, hi.y};
-            acc[db] = mfma_bf16(__builtin_bit_cast(bf16x8, w), am[ks], acc[db]);
-          }
+          for (int db = 0; db < D / 16; ++db) accA[db] = mfma16_bf16(vop(db, t), am[t], accA[db]);
+        } else if (t < nA + nB) {
+#pragma unroll
+          for (int db = 0; db < D / 16; ++db)
+            accB[db] = mfma16_bf16(vop(db, t - nA), am[t], accB[db]);
         }
       }
     }
 
-    if (active) {
-      bf16_t* dst = reinterpret_cast<bf16_t*>(a.O) +
-                    ((((size_t)b * a.Lc + l) * a.Hq + h) * S + r0) * (size_t)D;
-      store_tile_bf16<D>(acc, 1.0f, ost_all + wave * (32 * (D + 4)), dst, lane);
+    // 4. result registers: out[row i16 of the block][d = 16 db + 4 kq + v].  Both row blocks go
+    // through a wave-private LDS buffer so that global stores are contiguous 16-byte pieces.
+    bf16_t* ost = ost_all + wave * (32 * OS);
+#pragma unroll
+    for (int db = 0; db < D / 16; ++db) {
+      u32x2 wa, wb;
+      wa.x = pack_bf16(accA[db][0], accA[db][1]);
+      wa.y = pack_bf16(accA[db][2], accA[db][3]);
+      wb.x = pack_bf16(accB[db][0], accB[db][1]);
+      wb.y = pack_bf16(accB[db][2], accB[db][3]);
+      *reinterpret_cast<u32x2*>(ost + i16 * OS + 16 * db + 4 * kq) = wa;
+      *reinterpret_cast<u32x2*>(ost + (16 + i16) * OS + 16 * db + 4 * kq) = wb;
+    }
+    // LDS operations of one wave execute in order; only the compiler must keep the order
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    bf16_t* Ot = reinterpret_cast<bf16_t*>(a.O) +
+                 ((((size_t)b * a.Lc + l) * a.Hq + h) * S + (size_t)R * kChunk) * D;
+    constexpr int PIECES = 32 * D / 8;
+#pragma unroll
+    for (int it = 0; it < PIECES / kWave; ++it) {
+      const int p = it * kWave + lane;
+      const int row = p / (D / 8), c8 = p % (D / 8);
+      const bool low = row < 16;
+      if (low ? hasA : hasB) {
+        const u32x2* s = reinterpret_cast<const u32x2*>(ost + row * OS + 8 * c8);
+        u32x2 x = s[0], y = s[1];
+        u32x4 w = {x.x, x.y, y.x, y.y};
+        const int lrow = low ? 16 * rA + row : 16 * rB + row - 16;
+        // written once, never re-read by this kernel: streaming store
+        __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(Ot + (size_t)lrow * D + 8 * c8));
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+// Dense -> packed conversion of whole tiles (database build).  One workgroup per tile; a
+// thread moves 16-byte pieces: piece `lane` of packed block (r, cb) is map row 16 r + lane % 16,
+// columns 32 cb + 8 (lane / 16) .. + 8.
+__global__ __launch_bounds__(kThreads) void pack_maps_kernel(const bf16_t* __restrict__ dense,
+                                                             bf16_t* __restrict__ packed, int S,
+                                                             int causal) {
+  const int n16 = S >> 4, n32 = S >> 5;
+  const int nblk = packed_blocks(S, causal);
+  const bf16_t* src = dense + (size_t)blockIdx.x * S * S;
+  bf16_t* dst = packed + (size_t)blockIdx.x * nblk * 512;
+  const int lane = threadIdx.x & 63;
+  const int i16 = lane & 15, kq = lane >> 4;
+  for (int r = 0; r < n16; ++r) {
+    const int nc = causal ? ((r + 1) + 1) >> 1 : n32;
+    const int base = causal ? packed_prefix(r) : r * n32;
+    for (int cb = threadIdx.x >> 6; cb < nc; cb += kThreads / kWave) {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(src + (size_t)(16 * r + i16) * S + 32 * cb + 8 * kq);
+      *reinterpret_cast<u32x4*>(dst + (size_t)(base + cb) * 512 + lane * 8) = v;
     }
   }
 }
 
-// fp32 path (vector ALUs): small, correctness-first kernel for fp32 databases.
+// fp32 path (vector ALUs): small, correctness-first kernel for fp32 databases (dense layout).
 // One workgroup per (query, layer, head); thread t owns outputs (i, d) with
 // i*D + d = t, t + 256, ...; sums run over j in ascending order in fp32.
 __global__ __launch_bounds__(kThreads) void apply_f32_kernel(const ApplyArgs a, int D, int causal) {
@@ -166,6 +271,27 @@ static size_t apply_lds_bytes(int D) {
   return (size_t)(D * kVtStride + 4 * 32 * (D + 4)) * sizeof(bf16_t);
 }
 
+template <int D, bool CAUSAL, bool PACKED, bool PREFETCH>
+static hipError_t launch_bf16(const ApplyArgs& a, dim3 grid, hipStream_t stream) {
+  const size_t lds = apply_lds_bytes(D);
+  hipError_t e = ensure_lds<&apply_bf16_kernel<D, CAUSAL, PACKED, PREFETCH>>(lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((apply_bf16_kernel<D, CAUSAL, PACKED, PREFETCH>), grid, dim3(kThreads), lds,
+                     stream, a);
+  return hipGetLastError();
+}
+
+template <int D, bool CAUSAL>
+static hipError_t launch_bf16_dc(const ApplyArgs& a, dim3 grid, bool packed, bool prefetch,
+                                 hipStream_t stream) {
+  if (packed) {
+    return prefetch ? launch_bf16<D, CAUSAL, true, true>(a, grid, stream)
+                    : launch_bf16<D, CAUSAL, true, false>(a, grid, stream);
+  }
+  return prefetch ? launch_bf16<D, CAUSAL, false, true>(a, grid, stream)
+                  : launch_bf16<D, CAUSAL, false, false>(a, grid, stream);
+}
+
 // Host launcher.  Shapes were validated by the caller (api.hip).
 hipError_t launch_apply(const ApplyLaunch& p, hipStream_t stream) {
   ApplyArgs a;
@@ -189,19 +315,21 @@ hipError_t launch_apply(const ApplyLaunch& p, hipStream_t stream) {
   a.n_tiles = nb * p.Lc * (p.Hq / a.heads_per_wg);
   const int tiles8 = (a.n_tiles + 7) / 8 * 8;
   const dim3 grid((unsigned)(tiles8 * a.n_rblk));
-  const size_t lds = apply_lds_bytes(p.D);
-#define AC_LAUNCH_APPLY(DD, CC)                                                              \
-  do {                                                                                       \
-    hipError_t e = ensure_lds<&apply_bf16_kernel<DD, CC>>(lds);                              \
-    if (e != hipSuccess) return e;                                                           \
-    hipLaunchKernelGGL((apply_bf16_kernel<DD, CC>), grid, dim3(kThreads), lds, stream, a);   \
-  } while (0)
-  if (p.D == 64) {
-    if (p.causal) AC_LAUNCH_APPLY(64, true); else AC_LAUNCH_APPLY(64, false);
-  } else {
-    if (p.causal) AC_LAUNCH_APPLY(128, true); else AC_LAUNCH_APPLY(128, false);
-  }
-#undef AC_LAUNCH_APPLY
+  // a workgroup that walks several (head, chunk) steps prefetches the next step's map pieces
+  const bool prefetch = a.heads_per_wg > 1 || a.n_rblk > 1;
+  if (p.D == 64)
+    return p.causal ? launch_bf16_dc<64, true>(a, grid, p.packed, prefetch, stream)
+                    : launch_bf16_dc<64, false>(a, grid, p.packed, prefetch, stream);
+  return p.causal ? launch_bf16_dc<128, true>(a, grid, p.packed, prefetch, stream)
+                  : launch_bf16_dc<128, false>(a, grid, p.packed, prefetch, stream);
+}
+
+hipError_t launch_pack_maps(const void* dense, void* packed, int64_t n_tiles, int32_t S,
+                            int32_t causal, hipStream_t stream) {
+  if (n_tiles == 0) return hipSuccess;
+  hipLaunchKernelGGL(pack_maps_kernel, dim3((unsigned)n_tiles), dim3(kThreads), 0, stream,
+                     reinterpret_cast<const bf16_t*>(dense), reinterpret_cast<bf16_t*>(packed), S,
+                     causal);
   return hipGetLastError();
 }
 

@@ -26,11 +26,21 @@ struct ApplyLaunch {
   void* O;
   int32_t B, M, L, layer_begin, Lc, Hq, Hkv, S, D;
   int32_t causal, is_f32;
+  int32_t packed;        // bf16 only: maps are stored in the packed block layout
   int32_t fixed_entry;   // -1: index through hit[]
   int32_t n_list;        // queries in q_list (<= 32) when fixed_entry >= 0
   int32_t q_list[32];
 };
 hipError_t launch_apply(const ApplyLaunch& p, hipStream_t stream);
+hipError_t launch_pack_maps(const void* dense, void* packed, int64_t n_tiles, int32_t S,
+                            int32_t causal, hipStream_t stream);
+
+// Packed map layout: 16-row block r keeps its first packed_cols(r) blocks of 32 columns
+// (causal: ceil((r+1)/2); dense: all S/32), 512 elements each, row-block-major.
+__host__ __device__ inline int packed_prefix(int r) { return ((r + 1) >> 1) * ((r + 2) >> 1); }
+__host__ __device__ inline int packed_blocks(int S, int causal) {
+  return causal ? packed_prefix(S >> 4) : (S >> 4) * (S >> 5);
+}
 
 struct ExactLaunch {
   const void *Q, *K, *V;

@@ -44,13 +44,18 @@ def test_workspace_query_validates_without_a_gpu():
     from paper_2510_25979_amd import binding
     d = binding.DbDesc(n_emb=1000, emb_dim=256, emb_dtype=binding.AC_F16, metric=binding.AC_IP,
                        n_entries=1000, n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=64,
-                       seq_len=128, map_dtype=binding.AC_BF16, causal=1, maps_on_host=0)
+                       seq_len=128, map_dtype=binding.AC_BF16, causal=1, maps_on_host=0, map_layout=0)
     assert binding.attncache_workspace_bytes(d, 64, 1) > 0
     assert binding.attncache_workspace_bytes(d, 64, 4) > binding.attncache_workspace_bytes(d, 64, 1)
     import pytest
     with pytest.raises(binding.AttnCacheError) as e:
         binding.attncache_workspace_bytes(d, 64, 65)
     assert e.value.status == -5
+    assert binding.attncache_map_entry_bytes(d) == 2 * 4 * 128 * 128 * 2
+    d.map_layout = binding.AC_LAYOUT_PACKED
+    assert binding.attncache_map_entry_bytes(d) == 2 * 4 * 20 * 512 * 2      # 20 KiB per head
+    assert binding.packed_tile_elems(1024, True) == 32 * 33 * 512
+    assert binding.packed_tile_elems(96, False) == 96 * 96
     d.seq_len = 100
     with pytest.raises(binding.AttnCacheError) as e:
         binding.attncache_workspace_bytes(d, 64, 1)

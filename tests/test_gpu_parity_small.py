@@ -41,21 +41,37 @@ APPLY_CASES = [
     (2, 3, 1, 2, 2, 160, 64, False, 0, 1, torch.bfloat16),    # dense maps
     (2, 3, 1, 4, 2, 32, 128, False, 0, 1, torch.bfloat16),    # a single 32-row block
     (9, 4, 1, 3, 3, 64, 64, True, 0, 1, torch.bfloat16),      # tile count not a multiple of 8
+    (2, 2, 1, 2, 1, 416, 64, True, 0, 1, torch.bfloat16),     # four row blocks, ragged, 2 heads per V
+    (1, 2, 1, 1, 1, 1024, 128, True, 0, 1, torch.bfloat16),   # the long-sequence shape, one head
+    (2, 2, 1, 2, 2, 224, 128, False, 0, 1, torch.bfloat16),   # dense maps, two chunks, ragged
 ]
 
 
+def _build(ac, emb, maps, layout, causal, **kw):
+    """Database over dense maps, or over their packed form (converted on the GPU)."""
+    if layout == "dense":
+        return ac.attncache_build_db(emb.cuda(), maps.cuda(), causal=causal, **kw)
+    M, L, Hq, S, _ = maps.shape
+    packed = torch.empty(M, L, Hq, ac.packed_tile_elems(S, causal), dtype=torch.bfloat16, device="cuda")
+    ac.attncache_pack_maps(maps.cuda(), packed, causal=causal)
+    return ac.attncache_build_db(emb.cuda(), packed, causal=causal, seq_len=S, **kw)
+
+
+@pytest.mark.parametrize("layout", ["dense", "packed"])
 @pytest.mark.parametrize("case", APPLY_CASES, ids=lambda c: "B%d-M%d-L%d-H%d/%d-S%d-D%d-%s-%d+%d-%s" % (
     c[0], c[1], c[2], c[3], c[4], c[5], c[6], "causal" if c[7] else "dense", c[8], c[9],
     str(c[10]).split(".")[-1]))
-def test_apply_matches_oracle(ac, oracle_mod, case):
+def test_apply_matches_oracle(ac, oracle_mod, case, layout):
     B, M, L, Hq, Hkv, S, D, causal, lb, Lc, dt = case
+    if layout == "packed" and dt != torch.bfloat16:
+        pytest.skip("the packed layout exists for bf16 maps only")
     maps = _maps(M, L, Hq, S, dt, causal, 100 + S + D)
     V = torch.randn(B, Lc, Hkv, S, D, generator=_gen(200 + S)).to(dt)
     hit = torch.randint(0, M, (B,), generator=_gen(300 + B), dtype=torch.int32)
     if B > 2:
         hit[1] = -1                      # a miss: its output rows must stay untouched
     emb = torch.zeros(M, 16, dtype=torch.float32)
-    db = ac.attncache_build_db(emb.cuda(), maps.cuda(), n_kv_heads=Hkv, head_dim=D, causal=causal)
+    db = _build(ac, emb, maps, layout, causal, n_kv_heads=Hkv, head_dim=D)
     O = torch.full((B, Lc, Hq, S, D), 7.0, dtype=dt, device="cuda")
     ac.attncache_apply(db, hit.cuda(), V.cuda(), O, layer_begin=lb, layer_count=Lc)
     torch.cuda.synchronize()
@@ -68,11 +84,12 @@ def test_apply_matches_oracle(ac, oracle_mod, case):
     db.close()
 
 
-def test_apply_identity_map_returns_v_bit_exactly(ac):
+@pytest.mark.parametrize("layout", ["dense", "packed"])
+def test_apply_identity_map_returns_v_bit_exactly(ac, layout):
     S, D = 128, 64
     maps = torch.eye(S).expand(2, 1, 2, S, S).contiguous().to(torch.bfloat16)
     V = torch.randn(3, 1, 2, S, D, generator=_gen(1)).to(torch.bfloat16)
-    db = ac.attncache_build_db(torch.zeros(2, 16).cuda(), maps.cuda(), n_kv_heads=2, head_dim=D)
+    db = _build(ac, torch.zeros(2, 16), maps, layout, True, n_kv_heads=2, head_dim=D)
     O = torch.zeros(3, 1, 2, S, D, dtype=torch.bfloat16, device="cuda")
     ac.attncache_apply(db, torch.tensor([0, 1, 0], dtype=torch.int32).cuda(), V.cuda(), O)
     assert torch.equal(O.cpu(), V)
@@ -154,7 +171,7 @@ def test_reusing_own_map_reproduces_exact_attention_on_gpu(ac, oracle_mod):
     _, P = oracle_mod.attention_exact(parity.to_np(Q), parity.to_np(K), parity.to_np(V), return_map=True)
     maps = torch.from_numpy(oracle_mod.round_maps(P, oracle_mod.ROUND_BF16)).to(torch.bfloat16)
     maps = maps.reshape(B, 1, Hq, S, S).contiguous()
-    db = ac.attncache_build_db(torch.zeros(B, 16).cuda(), maps.cuda(), n_kv_heads=Hkv, head_dim=D)
+    db = _build(ac, torch.zeros(B, 16), maps, "packed", True, n_kv_heads=Hkv, head_dim=D)
     O_reuse = torch.empty(B, 1, Hq, S, D, dtype=torch.bfloat16, device="cuda")
     ac.attncache_apply(db, torch.arange(B, dtype=torch.int32).cuda(), V.reshape(B, 1, Hkv, S, D).cuda(), O_reuse)
     O_exact = torch.empty(B, Hq, S, D, dtype=torch.bfloat16, device="cuda")
