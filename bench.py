@@ -72,7 +72,7 @@ def main():
         sys.exit(3)
 
     from paper_2510_25979_amd import binding as ac
-    from paper_2510_25979_amd import synth
+    from paper_2510_25979_amd import synth, synthdb
 
     ac.lib()
     dev = torch.device("cuda:0")
@@ -92,25 +92,10 @@ def main():
     emb, raw, map_of = synth.make_embeddings(w, dev)
     q, planted = synth.make_queries(w, raw, dev)
     del raw
-    packed = args.layout == "packed" and w.map_dtype == "bf16"
-    tile = ac.packed_tile_elems(S, w.causal) if packed else S * S
-    db_bytes = w.n_entries * L * Hq * tile * (2 if w.map_dtype == "bf16" else 4)
-    log(f"workload {w.name}: {w.n_entries} map entries, dense {w.entry_bytes / 2**20:.0f} MiB each; "
-        f"stored {'packed' if packed else 'dense'}: {db_bytes / 2**30:.1f} GiB")
-    maps = torch.empty((w.n_entries, L, Hq, tile) if packed else (w.n_entries, L, Hq, S, S),
-                       dtype=dt, device=dev)
-    step_entries = max(1, (8 << 30) // w.entry_bytes)
-    scratch = torch.empty((min(step_entries, w.n_entries), L, Hq, S, S), dtype=dt, device=dev) \
-        if packed else None
-    for e0 in range(0, w.n_entries, step_entries):
-        e1 = min(w.n_entries, e0 + step_entries)
-        if packed:   # generate a dense slice, convert it into the database's storage layout
-            synth.fill_maps(w, scratch[:e1 - e0], first_entry=e0)
-            ac.attncache_pack_maps(scratch[:e1 - e0], maps[e0:e1], causal=w.causal)
-        else:
-            synth.fill_maps(w, maps[e0:e1], first_entry=e0)
-        torch.cuda.synchronize()
-        log(f"  maps filled: {e1}/{w.n_entries} ({time.time() - t0:.1f} s)")
+    log(f"workload {w.name}: {w.n_entries} map entries, dense {w.entry_bytes / 2**20:.0f} MiB each")
+    store = synthdb.SynthMapStore(w, dev, layout=args.layout, log=log)
+    maps, packed, db_bytes = store.maps, store.packed, store.stored_bytes
+    log(f"stored {'packed' if packed else 'dense'}: {db_bytes / 2**30:.1f} GiB")
     Q, K, V = synth.make_qkv(w, dev)
     O = torch.zeros(B, L, Hq, S, D, dtype=dt, device=dev)
     O_exact = torch.zeros(B, L, Hq, S, D, dtype=dt, device=dev)
@@ -234,16 +219,7 @@ def main():
         t1 = time.perf_counter()
         oracle.search(q.float().cpu().numpy(), emb.float().cpu().numpy(), k=w.k, theta=w.theta)
         t_search = time.perf_counter() - t1
-        dense_hits = torch.empty((len(sel), L, Hq, S, S), dtype=dt, device=dev)
-        for i, b in enumerate(sel):   # same seeded draw as the database slice holding this entry
-            e = int(hit_h[b])
-            e0 = e // step_entries * step_entries
-            n_slice = min(step_entries, w.n_entries - e0)
-            if packed:
-                synth.fill_maps(w, scratch[:n_slice], first_entry=e0)
-                dense_hits[i].copy_(scratch[e - e0])
-            else:
-                dense_hits[i].copy_(maps[e])
+        dense_hits = torch.stack([store.dense_entry(int(hit_h[b])) for b in sel])
         sub_maps = dense_hits.float().cpu().numpy()
         sub_V = V[sel].float().cpu().numpy()
         t1 = time.perf_counter()
