@@ -161,15 +161,28 @@ void apply_bf16_kernel(const ApplyArgs a) {
         u32x2 lo = src[0], hi = src[1];
         return u32x4{lo.x, lo.y, hi.x, hi.y};
       };
+      if (nA == 4 && nB == 4) {
+        // full chunk: both row blocks need the same four column blocks, so every V^T operand
+        // read from LDS feeds two products (LDS bandwidth, not HBM, would bound long rows else)
 #pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        if (t < nA) {
+        for (int t = 0; t < 4; ++t)
 #pragma unroll
-          for (int db = 0; db < D / 16; ++db) accA[db] = mfma16_bf16(vop(db, t), am[t], accA[db]);
-        } else if (t < nA + nB) {
+          for (int db = 0; db < D / 16; ++db) {
+            const u32x4 v = vop(db, t);
+            accA[db] = mfma16_bf16(v, am[t], accA[db]);
+            accB[db] = mfma16_bf16(v, am[t + 4], accB[db]);
+          }
+      } else {
 #pragma unroll
-          for (int db = 0; db < D / 16; ++db)
-            accB[db] = mfma16_bf16(vop(db, t - nA), am[t], accB[db]);
+        for (int t = 0; t < 8; ++t) {
+          if (t < nA) {
+#pragma unroll
+            for (int db = 0; db < D / 16; ++db) accA[db] = mfma16_bf16(vop(db, t), am[t], accA[db]);
+          } else if (t < nA + nB) {
+#pragma unroll
+            for (int db = 0; db < D / 16; ++db)
+              accB[db] = mfma16_bf16(vop(db, t - nA), am[t], accB[db]);
+          }
         }
       }
     }

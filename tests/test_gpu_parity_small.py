@@ -147,6 +147,25 @@ def test_exact_matches_oracle(ac, oracle_mod, case):
         assert (O[1] == 7.0).all()
 
 
+def test_exact_many_tiles_per_workgroup_with_routing(ac, oracle_mod):
+    # enough (batch, head) tiles that one workgroup walks several of them back to back, with
+    # some batch items routed away (their tiles are skipped in the middle of a walk)
+    B, H, S, D = 33, 128, 32, 64
+    g = _gen(11)
+    Q = torch.randn(B, H, S, D, generator=g).to(torch.bfloat16)
+    K = torch.randn(B, H, S, D, generator=g).to(torch.bfloat16)
+    V = torch.randn(B, H, S, D, generator=g).to(torch.bfloat16)
+    row_sel = torch.full((B,), -1, dtype=torch.int32)
+    row_sel[[0, 5, 6, 32]] = 1
+    O = torch.full((B, H, S, D), 7.0, dtype=torch.bfloat16, device="cuda")
+    ac.attention_exact(Q.cuda(), K.cuda(), V.cuda(), O, row_sel=row_sel.cuda())
+    torch.cuda.synchronize()
+    ref = oracle_mod.attention_exact(parity.to_np(Q), parity.to_np(K), parity.to_np(V),
+                                     row_sel=row_sel.numpy(), out=np.full((B, H, S, D), 7.0))
+    assert parity.max_abs_err(O, ref) <= 2e-2
+    assert (O[[0, 5, 6, 32]] == 7.0).all()
+
+
 def test_exact_large_logits_stay_finite(ac, oracle_mod):
     # peaked softmax: logits of magnitude ~60 must not overflow the online rescaling
     B, H, S, D = 1, 2, 256, 64
