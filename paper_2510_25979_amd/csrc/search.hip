@@ -148,6 +148,145 @@ __global__ __launch_bounds__(kThreads) void search_f16_kernel(const SearchArgs a
   }
 }
 
+// ---------------------------------------------------------------- phase 1, large batches
+// For more than 64 queries the roles are swapped: the QUERIES live in registers (each of the
+// four waves keeps QPW blocks of 32 queries as MFMA column operands for the whole kernel) and
+// the database rows stream through LDS in chunks of 64 rows.  Every row operand read from LDS
+// feeds QPW MFMAs per wave and is shared by the four waves, so LDS traffic is 4x the HBM
+// stream instead of 32x, and no cross-wave reduction is needed (a wave owns its queries).
+//
+// The chunks are copied global -> LDS directly (global_load_lds_dwordx4: no data registers; a
+// wave instruction fills 1 KiB of LDS contiguously, lane l at base + 16 l, whatever global
+// address lane l names), double-buffered in two separate LDS arrays so that the copy of chunk
+// c+1 runs while chunk c is multiplied.  Rows are stored unpadded; piece p (16 bytes) of row r
+// sits at position p ^ (r & 15) of its row, which makes the 16-byte operand reads of 32
+// consecutive rows conflict-free; the copy obtains the swizzle for free by choosing which
+// global piece each lane fetches.
+constexpr int kBigRows = 64;   // database rows per LDS chunk
+
+template <int KSMAX, int QPW>
+__global__ __launch_bounds__(kThreads, 2) void search_f16_big_kernel(const SearchArgs a) {
+  constexpr int E = 16 * KSMAX;               // this kernel is built for E = 128, 256, 512
+  constexpr int EQ = E / 8;                   // 16-byte pieces per row
+  constexpr int NDMA = kBigRows * EQ / kWave / 4;   // copy instructions per wave and chunk
+  __shared__ __attribute__((aligned(16))) f16_t buf0[kBigRows * E];
+  __shared__ __attribute__((aligned(16))) f16_t buf1[kBigRows * E];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int il = lane & 31, kh = lane >> 5;
+
+  // query operands: lane (il, kh) keeps q[q0 + 32 (QPW wave + j) + il][16 ks + 8 kh .. +8)
+  f16x8 qop[QPW][KSMAX];
+#pragma unroll
+  for (int j = 0; j < QPW; ++j) {
+    const int qi = 32 * (QPW * wave + j) + il;
+    const f16_t* qrow = reinterpret_cast<const f16_t*>(a.q) + (size_t)(a.q0 + min(qi, a.nq - 1)) * E + 8 * kh;
+#pragma unroll
+    for (int ks = 0; ks < KSMAX; ++ks) {
+      qop[j][ks] = *reinterpret_cast<const f16x8*>(qrow + 16 * ks);
+      if (qi >= a.nq) {   // padding query: all-zero operand
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qop[j][ks][e] = (f16_t)0.f;
+      }
+    }
+  }
+
+  const int row_begin = blockIdx.x * a.rows_per_wg;
+  const int row_end = min(row_begin + a.rows_per_wg, a.N);
+  const int n_chunk = (row_end - row_begin + kBigRows - 1) / kBigRows;
+  const f16_t* emb = reinterpret_cast<const f16_t*>(a.emb);
+
+  // copy chunk ch into buf: instruction k = wave + 4 i fills LDS slots [64 k, 64 k + 64) of the
+  // chunk (slot = row * EQ + position); rows past the end are clamped (masked when compared)
+  auto copy_in = [&](f16_t* buf, int ch) {
+#pragma unroll
+    for (int i = 0; i < NDMA; ++i) {
+      const int k = wave + 4 * i;
+      const int slot = kWave * k + lane;
+      const int row = slot / EQ, pos = slot % EQ;
+      const int piece = pos ^ (row & 15);
+      const int r = min(row_begin + ch * kBigRows + row, a.N - 1);
+      __builtin_amdgcn_global_load_lds(emb + (size_t)r * E + 8 * piece, buf + kWave * k * 8, 16, 0, 0);
+    }
+  };
+
+  float best_s[QPW];
+  int best_i[QPW];
+#pragma unroll
+  for (int j = 0; j < QPW; ++j) { best_s[j] = -INFINITY; best_i[j] = kIdxNone; }
+
+  auto compute = [&](const f16_t* buf, int ch) {
+    const int cbase = row_begin + ch * kBigRows;
+    const bool ragged = cbase + kBigRows > row_end;   // only the last chunk can be
+#pragma unroll
+    for (int rb = 0; rb < kBigRows / 32; ++rb) {
+      f32x16 acc[QPW];
+#pragma unroll
+      for (int j = 0; j < QPW; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+      const f16_t* erow = buf + (32 * rb + il) * E;
+#pragma unroll
+      for (int ks = 0; ks < KSMAX; ++ks) {
+        const f16x8 eop = *reinterpret_cast<const f16x8*>(erow + 8 * ((2 * ks + kh) ^ (il & 15)));
+#pragma unroll
+        for (int j = 0; j < QPW; ++j) acc[j] = mfma_f16(eop, qop[j][ks], acc[j]);
+      }
+      // acc[j][v] = <emb[r], q>.  A new best becomes rare as the scan proceeds, so first only the
+      // block maximum is compared; the position is looked up only when some lane improved.
+      // Rows ascend with v, rb and ch, so strict comparisons keep the lowest row among equals.
+      const int rbase = cbase + 32 * rb + 4 * kh;
+      if (ragged) {
+#pragma unroll
+        for (int j = 0; j < QPW; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            if (rbase + 8 * (v >> 2) + (v & 3) >= row_end) acc[j][v] = -INFINITY;
+      }
+#pragma unroll
+      for (int j = 0; j < QPW; ++j) {
+        float mx = acc[j][0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, acc[j][v]);
+        if (__any(mx > best_s[j])) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            if (acc[j][v] > best_s[j]) { best_s[j] = acc[j][v]; best_i[j] = rbase + 8 * (v >> 2) + (v & 3); }
+        }
+      }
+    }
+  };
+  // own copies landed (they are counted like loads), then everybody's
+  auto publish = [&]() {
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+  };
+
+  copy_in(buf0, 0);
+  publish();
+  for (int ch = 0; ch < n_chunk; ch += 2) {
+    if (ch + 1 < n_chunk) copy_in(buf1, ch + 1);
+    compute(buf0, ch);
+    publish();
+    if (ch + 1 < n_chunk) {
+      if (ch + 2 < n_chunk) copy_in(buf0, ch + 2);
+      compute(buf1, ch + 1);
+      publish();
+    }
+  }
+  // combine the two lane halves; every wave owns its queries, nothing else to merge
+#pragma unroll
+  for (int j = 0; j < QPW; ++j) {
+    const float so = __shfl_xor(best_s[j], 32);
+    const int io = __shfl_xor(best_i[j], 32);
+    if (ranks_before(so, io, best_s[j], best_i[j])) { best_s[j] = so; best_i[j] = io; }
+    const int qi = 32 * (QPW * wave + j) + il;
+    if (kh == 0 && qi < a.nq) {
+      a.part_s[(size_t)(a.q0 + qi) * a.G + blockIdx.x] = best_s[j];
+      a.part_i[(size_t)(a.q0 + qi) * a.G + blockIdx.x] = best_i[j];
+    }
+  }
+}
+
 // ------------------------------------------------------------- vector-ALU scoring
 template <typename T>
 __device__ __forceinline__ float load_as_float(const T* p) { return (float)(*p); }
@@ -288,15 +427,25 @@ __global__ __launch_bounds__(kThreads) void finalize_topk_kernel(const SearchArg
 }
 
 // ------------------------------------------------------------------- host side
-static void search_plan(int32_t N, int32_t is_mfma, int32_t* rows_per_wg, int32_t* G) {
+enum { kModeValu = 0, kModeMfma = 1, kModeMfmaBig = 2 };
+constexpr int kBigBatch = 64;   // above this many queries the query-stationary kernel is used
+
+static void search_plan(int32_t N, int32_t mode, int32_t* rows_per_wg, int32_t* G) {
   int rpw;
-  if (is_mfma) {
+  if (mode == kModeMfma) {
     // 128 rows per pass of a workgroup; more passes per workgroup for large databases so that
     // the query tile staged in LDS is amortised, while keeping >= ~1000 workgroups
     long c = ((long)N + 128L * 1024 - 1) / (128L * 1024);
     if (c < 1) c = 1;
     if (c > 8) c = 8;
     rpw = 128 * (int)c;
+  } else if (mode == kModeMfmaBig) {
+    // chunks of 64 rows; enough chunks per workgroup to amortise loading the queries into
+    // registers, while keeping ~2000 workgroups
+    long c = ((long)N + 64L * 2048 - 1) / (64L * 2048);
+    if (c < 1) c = 1;
+    if (c > 16) c = 16;
+    rpw = kBigRows * (int)c;
   } else {
     rpw = kValuRowsPerWg;
   }
@@ -308,19 +457,29 @@ static bool use_mfma(int32_t is_f16, int32_t metric, int32_t E) {
   return is_f16 && metric == 0 && E % 16 == 0 && E <= 512;
 }
 
+static int search_mode(int32_t is_f16, int32_t metric, int32_t E, int32_t B) {
+  if (!use_mfma(is_f16, metric, E)) return kModeValu;
+  const bool big_shape = E == 128 || E == 256 || E == 512;   // instantiated widths
+  return (B > kBigBatch && big_shape) ? kModeMfmaBig : kModeMfma;
+}
+
 size_t search_workspace_bytes(int32_t N, int32_t E, int32_t B, int32_t k, int32_t is_f16) {
-  // the plan depends on the metric only through the path choice; size for the larger of both
+  // the metric is not known here: size for the larger of the paths this (dtype, E, B) can take
   size_t need = 0;
-  for (int mfma = 0; mfma < 2; ++mfma) {
-    if (mfma && !use_mfma(is_f16, 0, E)) continue;
+  for (int metric = 0; metric < 2; ++metric) {
     int32_t rpw, G;
-    search_plan(N, mfma, &rpw, &G);
-    size_t bytes = (size_t)B * G * 8;
-    bytes = (bytes + 255) / 256 * 256;
+    search_plan(N, search_mode(is_f16, metric, E, B), &rpw, &G);
+    size_t bytes = ((size_t)B * G * 8 + 255) / 256 * 256;
     if (k > 1) bytes += (size_t)B * k * rpw * 4;
     if (bytes > need) need = bytes;
   }
   return need + 256;
+}
+
+template <int KSMAX, int QPW>
+static hipError_t launch_f16_big(const SearchArgs& a, dim3 grid, hipStream_t stream) {
+  hipLaunchKernelGGL((search_f16_big_kernel<KSMAX, QPW>), grid, dim3(kThreads), 0, stream, a);
+  return hipGetLastError();
 }
 
 template <int KSMAX, int NQB>
@@ -353,8 +512,9 @@ hipError_t launch_search(const SearchLaunch& p, hipStream_t stream) {
   a.N = p.N; a.E = p.E; a.B = p.B; a.k = p.k; a.metric = p.metric;
   a.threshold = p.threshold;
   a.idx = p.idx; a.score = p.score; a.hit = p.hit;
-  const bool mfma = use_mfma(p.is_f16, p.metric, p.E);
-  search_plan(p.N, mfma, &a.rows_per_wg, &a.G);
+  const int mode = search_mode(p.is_f16, p.metric, p.E, p.B);
+  const bool mfma = mode == kModeMfma;
+  search_plan(p.N, mode, &a.rows_per_wg, &a.G);
   unsigned char* ws = reinterpret_cast<unsigned char*>(p.ws);
   size_t part_bytes = ((size_t)p.B * a.G * 8 + 255) / 256 * 256;
   a.part_s = reinterpret_cast<float*>(ws);
@@ -362,7 +522,23 @@ hipError_t launch_search(const SearchLaunch& p, hipStream_t stream) {
   a.cand = reinterpret_cast<float*>(ws + part_bytes);
   a.q0 = 0; a.nq = p.B;
 
-  if (mfma) {
+  if (mode == kModeMfmaBig) {
+    // query super-blocks of 128 * QPW queries (4 waves x QPW blocks of 32); two blocks per wave
+    // only while the query operands fit in the register file (E <= 256)
+    const int ksmax = p.E <= 128 ? 8 : (p.E <= 256 ? 16 : 32);
+    const int qpw_max = p.E <= 256 ? 2 : 1;
+    const dim3 grid((unsigned)a.G);
+    for (int q0 = 0; q0 < p.B; q0 += 128 * qpw_max) {
+      a.q0 = q0;
+      a.nq = p.B - q0 < 128 * qpw_max ? p.B - q0 : 128 * qpw_max;
+      const int qpw = a.nq > 128 ? 2 : 1;
+      hipError_t e;
+      if (ksmax == 8) e = qpw == 2 ? launch_f16_big<8, 2>(a, grid, stream) : launch_f16_big<8, 1>(a, grid, stream);
+      else if (ksmax == 16) e = qpw == 2 ? launch_f16_big<16, 2>(a, grid, stream) : launch_f16_big<16, 1>(a, grid, stream);
+      else e = launch_f16_big<32, 1>(a, grid, stream);
+      if (e != hipSuccess) return e;
+    }
+  } else if (mfma) {
     // query super-blocks of 32 * nqb queries; the staged tile must fit in LDS
     const int ksmax = p.E <= 128 ? 8 : (p.E <= 256 ? 16 : 32);
     int max_nqb = 8;
