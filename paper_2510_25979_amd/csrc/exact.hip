@@ -50,7 +50,8 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 4 : 2)) void exact_bf16_kernel
   bf16_t* vt = ks_lds + kChunk * KS;
   bf16_t* ost_all = a.heads_per_wg > 1 ? vt + D * kVtStride : ks_lds;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
   const int il = lane & 31, kh = lane >> 5;
   const int S = a.S, g = a.Hq / a.Hkv;
   const int bid = blockIdx.x;

@@ -69,7 +69,8 @@ __global__ __launch_bounds__(kThreads) void search_f16_kernel(const SearchArgs a
   float* red_s = reinterpret_cast<float*>(smem + (size_t)32 * NQB * QS * 2);  // [4][32 NQB]
   int* red_i = reinterpret_cast<int*>(red_s + 4 * 32 * NQB);
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
   const int il = lane & 31, kh = lane >> 5;
   const int nks = E >> 4;
 
@@ -171,7 +172,8 @@ __global__ __launch_bounds__(kThreads, 2) void search_f16_big_kernel(const Searc
   constexpr int NDMA = kBigRows * EQ / kWave / 4;   // copy instructions per wave and chunk
   __shared__ __attribute__((aligned(16))) f16_t buf0[kBigRows * E];
   __shared__ __attribute__((aligned(16))) f16_t buf1[kBigRows * E];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
   const int il = lane & 31, kh = lane >> 5;
 
   // query operands: lane (il, kh) keeps q[q0 + 32 (QPW wave + j) + il][16 ks + 8 kh .. +8)
