@@ -114,7 +114,8 @@ __device__ __forceinline__ void store_tile_bf16(const f32x16 (&acc)[D / 32], flo
     u32x4 w;
     u32x2 a = s[0], b = s[1];
     w.x = a.x; w.y = a.y; w.z = b.x; w.w = b.y;
-    *reinterpret_cast<u32x4*>(dst + (size_t)row * D + 8 * c8) = w;
+    // written once, not re-read by the writing kernel: streaming store
+    __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(dst + (size_t)row * D + 8 * c8));
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();

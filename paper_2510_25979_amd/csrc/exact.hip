@@ -27,7 +27,7 @@
 namespace ac {
 
 constexpr int kKPad = 8;   // elements of padding per staged K row (keeps 16-byte alignment)
-constexpr int kOPass = 32; // output columns staged per pass
+constexpr int kOPass = 64; // output columns staged per pass (16 rows at a time)
 constexpr int kOStride = kOPass + 4;
 
 
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 4 : 2)) void exact_bf16_kernel
   constexpr int KS = D + kKPad;
   bf16_t* ks_lds = reinterpret_cast<bf16_t*>(smem);
   bf16_t* vt = ks_lds + kChunk * KS;
-  bf16_t* ost_all = a.heads_per_wg > 1 ? vt + D * kVtStride : ks_lds;
+  bf16_t* ost_all = vt + D * kVtStride;   // [4][16][kOStride], present only when heads_per_wg > 1
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
@@ -182,32 +182,46 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 4 : 2)) void exact_bf16_kernel
     if (active) {
       const float inv = 1.0f / (l_run + __shfl_xor(l_run, 32));
       bf16_t* Oh = reinterpret_cast<bf16_t*>(a.O) + (((size_t)b * a.Hq + h) * S + r0) * (size_t)D;
-      {
-        bf16_t* ost = ost_all + wave * (32 * kOStride);
+      if (a.heads_per_wg == 1) {
+        // K is no longer needed: the whole 32 x D tile is staged on top of it and leaves as
+        // complete contiguous rows (measurably better than 64-byte row segments)
+        store_tile_bf16<D>(acc, inv, ks_lds + wave * (32 * (D + 4)), Oh, lane);
+      } else {
+        // K must survive for the next head: a small wave-private buffer takes 16 rows x 64
+        // columns per pass, so every global store still covers whole 128-byte lines
+        bf16_t* ost = ost_all + wave * (16 * kOStride);
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db) {
+        for (int rh = 0; rh < 2; ++rh)
 #pragma unroll
-          for (int vq = 0; vq < 4; ++vq) {
-            u32x2 w;
-            w.x = pack_bf16(acc[db][4 * vq] * inv, acc[db][4 * vq + 1] * inv);
-            w.y = pack_bf16(acc[db][4 * vq + 2] * inv, acc[db][4 * vq + 3] * inv);
-            *reinterpret_cast<u32x2*>(ost + il * kOStride + 8 * vq + 4 * kh) = w;
+          for (int dh = 0; dh < D / 64; ++dh) {
+            if ((il >> 4) == rh) {
+#pragma unroll
+              for (int dbp = 0; dbp < 2; ++dbp)
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                  const f32x16& t = acc[2 * dh + dbp];
+                  u32x2 w;
+                  w.x = pack_bf16(t[4 * vq] * inv, t[4 * vq + 1] * inv);
+                  w.y = pack_bf16(t[4 * vq + 2] * inv, t[4 * vq + 3] * inv);
+                  *reinterpret_cast<u32x2*>(ost + (il & 15) * kOStride + 32 * dbp + 8 * vq + 4 * kh) = w;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+              const int p = it * kWave + lane;
+              const int row = p >> 3, c8 = p & 7;
+              const u32x2* sp = reinterpret_cast<const u32x2*>(ost + row * kOStride + 8 * c8);
+              u32x2 lo = sp[0], hi = sp[1];
+              __builtin_nontemporal_store(
+                  u32x4{lo.x, lo.y, hi.x, hi.y},
+                  reinterpret_cast<u32x4*>(Oh + (size_t)(16 * rh + row) * D + 64 * dh + 8 * c8));
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
           }
-          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-          __builtin_amdgcn_wave_barrier();
-          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-          for (int it = 0; it < 2; ++it) {
-            const int p = it * kWave + lane;
-            const int row = p >> 2, c8 = p & 3;
-            const u32x2* sp = reinterpret_cast<const u32x2*>(ost + row * kOStride + 8 * c8);
-            u32x2 lo = sp[0], hi = sp[1];
-            __builtin_nontemporal_store(u32x4{lo.x, lo.y, hi.x, hi.y},
-                                        reinterpret_cast<u32x4*>(Oh + (size_t)row * D + 32 * db + 8 * c8));
-          }
-          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-          __builtin_amdgcn_wave_barrier();
-        }
       }
     }
   }
@@ -255,7 +269,7 @@ __global__ __launch_bounds__(kWave) void exact_f32_kernel(const ExactArgs a, int
 
 static size_t exact_lds_bytes(int D, int heads_per_wg) {
   const size_t kv = (size_t)(kChunk * (D + kKPad) + D * kVtStride) * sizeof(bf16_t);
-  return heads_per_wg > 1 ? kv + (size_t)4 * 32 * kOStride * sizeof(bf16_t) : kv;
+  return heads_per_wg > 1 ? kv + (size_t)4 * 16 * kOStride * sizeof(bf16_t) : kv;
 }
 
 template <int D, bool CAUSAL>
