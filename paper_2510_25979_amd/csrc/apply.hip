@@ -226,6 +226,211 @@ void apply_bf16_kernel(const ApplyArgs a) {
   }
 }
 
+// Long sequences (S > 128).  The 16x16x32 matrix instruction runs at half the rate of 32x32x16 on
+// this chip (measured 1.3 vs 2.0 PFLOP/s), which does not matter for one 128-column chunk per
+// tile but bounds the reuse product once a workgroup walks many full chunks.  Here a wave owns
+// one 32-row block of the 128-row block and uses v_mfma_f32_32x32x16_bf16.  Only the diagonal
+// chunk is unbalanced (wave w needs 2 (w + 1) of its 8 column steps).
+//
+// V is not transposed by the ALUs here.  Each 128-key chunk is copied global -> LDS directly
+// (global_load_lds_dwordx4, no data registers), row-major, into one of two LDS buffers, so the
+// copy of chunk c+1 and the map pieces of chunk c+1 are in flight while chunk c is multiplied;
+// the matrix operand is then fetched with the transposing LDS read (ds_read_b64_tr_b16): in a
+// group of 16 lanes, lane i supplies the address of four consecutive d of key j(i/4) and lane
+// t receives, for ITS d, the four keys j(0..3) -- exactly the operand layout, no shuffles.
+// Rows are stored unpadded; 16-byte piece p of key row r sits at position p ^ 2 (r & (D/16 - 1)), which
+// spreads the four key rows one group touches over distinct banks; the copy applies the
+// swizzle by choosing which global piece each lane fetches.
+template <int D, bool CAUSAL, bool PACKED>
+__global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const ApplyArgs a) {
+  constexpr int PPR = D / 8;                       // 16-byte pieces per V row
+  constexpr int NCOPY = kChunk * PPR / kWave / 4;  // copy instructions per wave and chunk
+  constexpr int kSwz = PPR / 2 - 1;                // swizzle mask: 2 (r & kSwz) < PPR
+  __shared__ __attribute__((aligned(16))) bf16_t vb0[kChunk * D];
+  __shared__ __attribute__((aligned(16))) bf16_t vb1[kChunk * D];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: branches on it stay uniform
+  const int il = lane & 31, kh = lane >> 5;
+
+  const int bid = blockIdx.x;
+  const int tile = (bid >> 3) / a.n_rblk * 8 + (bid & 7);
+  const int R = a.n_rblk - 1 - (bid >> 3) % a.n_rblk;
+  if (tile >= a.n_tiles) return;
+  const int h = tile % a.Hq;
+  const int l = (tile / a.Hq) % a.Lc;
+  const int bslot = tile / (a.Hq * a.Lc);
+  int b, entry;
+  if (a.fixed_entry >= 0) {
+    b = a.q_list[bslot];
+    entry = 0;
+  } else {
+    b = bslot;
+    entry = a.hit[b];
+    if (entry < 0 || entry >= a.M) return;   // miss (or invalid index): O[b] untouched
+  }
+
+  const int S = a.S, g = a.Hq / a.Hkv;
+  const int n32 = S >> 5;
+  const size_t tile_elems = PACKED ? (size_t)packed_blocks(S, CAUSAL) * 512 : (size_t)S * S;
+  const bf16_t* Vsrc = reinterpret_cast<const bf16_t*>(a.V) +
+                       (((size_t)b * a.Lc + l) * a.Hkv + h / g) * (size_t)S * D;
+  const bf16_t* At = reinterpret_cast<const bf16_t*>(a.maps) +
+                     (((size_t)entry * a.L + (a.layer_begin + l)) * a.Hq + h) * tile_elems;
+
+  const int rb32 = 4 * R + wave;            // 32-row block of this wave
+  const bool active = 32 * rb32 < S;
+  const int n_chunk = CAUSAL ? R + 1 : (S + kChunk - 1) / kChunk;
+
+  // 16-byte operand piece of column step ks (16 columns, counted from column 0) for this lane:
+  // map row 32 rb32 + il, columns 16 ks + 8 kh .. + 8
+  auto piece = [&](int ks) -> const u32x4* {
+    if (PACKED) {
+      const int r16 = 2 * rb32 + (il >> 4);
+      const int blk = (CAUSAL ? packed_prefix(r16) : r16 * n32) + (ks >> 1);
+      return reinterpret_cast<const u32x4*>(At + (size_t)blk * 512 +
+                                            ((2 * (ks & 1) + kh) * 16 + (il & 15)) * 8);
+    }
+    return reinterpret_cast<const u32x4*>(At + (size_t)(32 * rb32 + il) * S + 16 * ks + 8 * kh);
+  };
+  // column steps of chunk c this wave needs
+  auto steps = [&](int c) {
+    if (!active) return 0;
+    const int nk = min(kChunk, S - c * kChunk) >> 4;
+    return (CAUSAL && c == R) ? min(nk, 2 * (wave + 1)) : nk;
+  };
+  auto full = [&](int c) {   // uniform over the workgroup: every wave takes all 8 steps
+    return !(CAUSAL && c == R) && S - c * kChunk >= kChunk && 32 * (4 * R + 3) < S;
+  };
+  // map pieces of chunk c into am.  Every lane loads 8 pieces whatever it needs: a step beyond
+  // the wave's last one repeats that last piece (same cache lines, no extra memory traffic,
+  // never multiplied), which keeps the loads free of per-wave control flow.
+  auto issue = [&](int c, u32x4 (&am)[8]) {
+    const int nks = steps(c);
+    if (nks == 0) return;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) am[ks] = *piece(8 * c + min(ks, nks - 1));
+  };
+  // copy key rows [128 c, 128 c + nj) of V into buf: instruction k = wave + 4 i fills LDS slots
+  // [64 k, 64 k + 64) (slot = row * PPR + position), i.e. rows [k 64/PPR, (k + 1) 64/PPR).
+  // Row and position of a lane's slot differ between instructions only by whole multiples of
+  // 2048 elements on both sides, so one 32-bit lane offset serves all of them.  Rows past the
+  // end of V (ragged last chunk) repeat the last row: finite values that are never multiplied.
+  const int slot0 = kWave * wave + lane;
+  const unsigned copy_off = (unsigned)((slot0 / PPR) * D + 8 * ((slot0 % PPR) ^ (2 * ((slot0 / PPR) & kSwz))));
+  auto copy_v = [&](bf16_t* buf, int c) {
+    const int nj = min(kChunk, S - c * kChunk);
+    const bf16_t* src = Vsrc + (size_t)c * kChunk * D;
+    if (nj == kChunk) {
+#pragma unroll
+      for (int i = 0; i < NCOPY; ++i)
+        __builtin_amdgcn_global_load_lds(src + (copy_off + 2048u * i), buf + kWave * 8 * (wave + 4 * i),
+                                         16, 0, 0);
+    } else {
+#pragma unroll
+      for (int i = 0; i < NCOPY; ++i) {
+        const int slot = slot0 + 4 * kWave * i;
+        const int row = slot / PPR, pos = slot % PPR;
+        const int src_piece = pos ^ (2 * (row & kSwz));
+        __builtin_amdgcn_global_load_lds(src + (size_t)min(row, nj - 1) * D + 8 * src_piece,
+                                         buf + kWave * 8 * (wave + 4 * i), 16, 0, 0);
+      }
+    }
+  };
+
+  f32x16 acc[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+
+  // transposing operand fetch: rows d = 32 db + il of V^T, contraction slots (kh, e) = key
+  // 16 ks + 8 kh + e.  Lane i of a 16-lane group names key row 16 ks + 8 kh + i / 4 (+ 4 for
+  // the second half) and the four d starting at 32 db + 16 (il / 16) + 4 (i % 4).  The row's
+  // swizzle only depends on (key & 7), i.e. not on ks: one element offset per (half, db) is
+  // kept in a register and ks enters as a constant.
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  int voff[2][D / 32];
+  {
+    const int t = lane & 15;
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db) {
+        const int j = 8 * kh + 4 * half + (t >> 2);               // key row for ks = 0
+        const int d0 = 32 * db + 16 * (il >> 4) + 4 * (t & 3);     // first of this lane's four d
+        voff[half][db] = j * D + 8 * ((d0 >> 3) ^ (2 * (j & kSwz))) + (d0 & 7);
+      }
+  }
+  auto vop = [&](const bf16_t* buf, int db, int ks) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(buf + voff[0][db] + 16 * ks * D));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(buf + voff[1][db] + 16 * ks * D));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    s16x8 w = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, w);
+  };
+  // Products of chunk c.  The scheduling fences keep the compiler from hoisting every operand
+  // read of a chunk in front of the first product (more registers than the file has).
+  auto compute = [&](const bf16_t* buf, int c, const u32x4 (&am)[8]) {
+    if (full(c)) {
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+          acc[db] = mfma_bf16(vop(buf, db, ks), __builtin_bit_cast(bf16x8, am[ks]), acc[db]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    } else {
+      const int nks = steps(c);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        if (ks < nks) {
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db)
+            acc[db] = mfma_bf16(vop(buf, db, ks), __builtin_bit_cast(bf16x8, am[ks]), acc[db]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  };
+  // Software pipeline over chunks, unrolled by two so that buffers and register sets alternate
+  // without copies: while chunk c is multiplied out of (vb0, am0), the copy of V chunk c + 1
+  // into vb1 and the map pieces of chunk c + 1 into am1 are in flight, and vice versa.
+  // publish(): this wave's copies and loads have landed (copies are counted like loads), then
+  // the barrier makes every wave's part of the V chunk visible and retires the other buffer.
+  auto publish = [&]() {
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+  };
+  auto prefetch = [&](bf16_t* buf, int c, u32x4 (&am)[8]) {
+    copy_v(buf, c);
+    issue(c, am);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  u32x4 am0[8], am1[8];
+  prefetch(vb0, 0, am0);
+  for (int c = 0; c < n_chunk; c += 2) {
+    publish();
+    if (c + 1 < n_chunk) prefetch(vb1, c + 1, am1);
+    compute(vb0, c, am0);
+    if (c + 1 < n_chunk) {
+      publish();
+      if (c + 2 < n_chunk) prefetch(vb0, c + 2, am0);
+      compute(vb1, c + 1, am1);
+    }
+  }
+  __syncthreads();   // every wave is done with both V buffers: they now stage the output
+  if (active) {
+    bf16_t* dst = reinterpret_cast<bf16_t*>(a.O) +
+                  ((((size_t)b * a.Lc + l) * a.Hq + h) * S + 32 * rb32) * (size_t)D;
+    bf16_t* ost = ((wave & 2) ? vb1 : vb0) + (wave & 1) * (32 * (D + 4));
+    store_tile_bf16<D>(acc, 1.0f, ost, dst, lane);
+  }
+}
+
 // Dense -> packed conversion of whole tiles (database build).  One workgroup per tile; a
 // thread moves 16-byte pieces: piece `lane` of packed block (r, cb) is map row 16 r + lane % 16,
 // columns 32 cb + 8 (lane / 16) .. + 8.
@@ -305,6 +510,21 @@ static hipError_t launch_bf16_dc(const ApplyArgs& a, dim3 grid, bool packed, boo
                   : launch_bf16<D, CAUSAL, false, false>(a, grid, stream);
 }
 
+template <int D, bool CAUSAL, bool PACKED>
+static hipError_t launch_long(const ApplyArgs& a, dim3 grid, hipStream_t stream) {
+  hipLaunchKernelGGL((apply_bf16_long_kernel<D, CAUSAL, PACKED>), grid, dim3(kThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_long_d(const ApplyArgs& a, dim3 grid, bool causal, bool packed,
+                                hipStream_t stream) {
+  if (causal) return packed ? launch_long<D, true, true>(a, grid, stream)
+                            : launch_long<D, true, false>(a, grid, stream);
+  return packed ? launch_long<D, false, true>(a, grid, stream)
+                : launch_long<D, false, false>(a, grid, stream);
+}
+
 // Host launcher.  Shapes were validated by the caller (api.hip).
 hipError_t launch_apply(const ApplyLaunch& p, hipStream_t stream) {
   ApplyArgs a;
@@ -328,8 +548,11 @@ hipError_t launch_apply(const ApplyLaunch& p, hipStream_t stream) {
   a.n_tiles = nb * p.Lc * (p.Hq / a.heads_per_wg);
   const int tiles8 = (a.n_tiles + 7) / 8 * 8;
   const dim3 grid((unsigned)(tiles8 * a.n_rblk));
-  // a workgroup that walks several (head, chunk) steps prefetches the next step's map pieces
-  const bool prefetch = a.heads_per_wg > 1 || a.n_rblk > 1;
+  if (a.n_rblk > 1)   // long rows: 32-row blocks per wave, full-rate matrix instruction
+    return p.D == 64 ? launch_long_d<64>(a, grid, p.causal, p.packed, stream)
+                     : launch_long_d<128>(a, grid, p.causal, p.packed, stream);
+  // a workgroup that walks several heads prefetches the next head's map pieces
+  const bool prefetch = a.heads_per_wg > 1;
   if (p.D == 64)
     return p.causal ? launch_bf16_dc<64, true>(a, grid, p.packed, prefetch, stream)
                     : launch_bf16_dc<64, false>(a, grid, p.packed, prefetch, stream);
