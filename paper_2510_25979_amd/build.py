@@ -11,7 +11,7 @@ HEADERS = ["common.hpp", "launch.hpp", os.path.join("..", "..", "include", "attn
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 instructions
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall",
-         "-Wno-unused-command-line-argument"]
+         "-Wno-unused-command-line-argument", "-Wl,-z,defs"]
 
 
 def stale() -> bool:

@@ -227,6 +227,243 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 4 : 2)) void exact_bf16_kernel
   }
 }
 
+// Long sequences (S > 128): one workgroup = one (batch item, query head, block of 128 query
+// rows) that walks the keys in chunks of 64.  Same transposed products and in-register P as
+// above; what differs is how K and V reach the matrix cores:
+//   * each chunk of K and of V is copied global -> LDS directly (global_load_lds_dwordx4, no
+//     data registers, no ALU work), row-major, into one of two stages, so the copy of chunk
+//     c + 1 is in flight while chunk c is multiplied and one barrier per chunk suffices;
+//   * rows are unpadded; the copy permutes the 16-byte pieces of a row (a lane picks which
+//     global piece lands in its LDS slot) so that the operand reads spread over all banks:
+//     K piece p of row r sits at p ^ k_piece_swizzle(r), V piece p of row r at p ^ 2 (r mod D/16);
+//   * the V^T operand is fetched with the transposing LDS read (ds_read_b64_tr_b16): in a
+//     group of 16 lanes, lane i names four consecutive d of key j(i / 4) and lane t receives,
+//     for its own d, the four keys j(0..3);
+//   * the two 32-key blocks of a chunk share one softmax step (one maximum exchange, one
+//     rescale test per 64 keys), which also gives the scheduler two independent chains.
+constexpr int kLChunk = 64;
+
+// permutation of the 16-byte pieces of staged K row r (unchanged by r + 256 / (D / 8))
+template <int D>
+__host__ __device__ constexpr int k_piece_swizzle(int r) {
+  return D == 128 ? (r & 15) : ((r >> 1) & 7);
+}
+
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(kThreads, 2) void exact_bf16_long_kernel(const ExactArgs a) {
+  constexpr int PPR = D / 8;                          // 16-byte pieces per row
+  constexpr int NCOPY = kLChunk * PPR / kWave / 4;    // copy instructions per wave, tensor, chunk
+  constexpr int kVSwz = PPR / 2 - 1;
+  __shared__ __attribute__((aligned(16))) bf16_t kb0[kLChunk * D];
+  __shared__ __attribute__((aligned(16))) bf16_t vb0[kLChunk * D];
+  __shared__ __attribute__((aligned(16))) bf16_t kb1[kLChunk * D];
+  __shared__ __attribute__((aligned(16))) bf16_t vb1[kLChunk * D];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
+  const int il = lane & 31, kh = lane >> 5;
+  const int S = a.S, g = a.Hq / a.Hkv;
+  const int bid = blockIdx.x;
+  const int slot = bid >> 3;
+  const int per_u = g * a.n_rblk;
+  const int u = (slot / per_u) * 8 + (bid & 7);
+  if (u >= a.n_kvtiles) return;
+  const int h = (u % a.Hkv) * g + (slot % per_u) / a.n_rblk;
+  const int R = a.n_rblk - 1 - (slot % per_u) % a.n_rblk;   // heaviest row blocks first
+  const int b = u / a.Hkv;
+  if (a.row_sel && a.row_sel[b] >= 0) return;
+
+  const bf16_t* Ksrc = reinterpret_cast<const bf16_t*>(a.K) + (size_t)u * S * D;
+  const bf16_t* Vsrc = reinterpret_cast<const bf16_t*>(a.V) + (size_t)u * S * D;
+  const int last_key = CAUSAL ? min(S, kChunk * (R + 1)) : S;
+  const int n_chunk = (last_key + kLChunk - 1) / kLChunk;
+  const int rw = wave;
+  const int r0 = R * kChunk + 32 * rw;
+  const bool active = r0 < S;
+
+
+  // ---- copies: instruction k = wave + 4 i fills LDS slots [64 k, 64 k + 64), slot = row * PPR +
+  // position.  From one instruction to the next, row grows by 256 / PPR (which leaves both
+  // permutations unchanged) and both addresses by 2048 elements: one lane offset per tensor.
+  const int slot0 = kWave * wave + lane;
+  const int crow = slot0 / PPR, cpos = slot0 % PPR;
+  const int kpiece = cpos ^ k_piece_swizzle<D>(crow);   // global piece that lands in this lane's slot
+  const int vpiece = cpos ^ (2 * (crow & kVSwz));
+  const unsigned kcopy_off = (unsigned)(crow * D + 8 * kpiece);
+  const unsigned vcopy_off = (unsigned)(crow * D + 8 * vpiece);
+  auto prefetch = [&](bf16_t* kb, bf16_t* vb, int c) {
+    const int nj = min(kLChunk, S - c * kLChunk);
+    const bf16_t* ksrc = Ksrc + (size_t)c * kLChunk * D;
+    const bf16_t* vsrc = Vsrc + (size_t)c * kLChunk * D;
+    if (nj == kLChunk) {
+#pragma unroll
+      for (int i = 0; i < NCOPY; ++i) {
+        __builtin_amdgcn_global_load_lds(ksrc + (kcopy_off + 2048u * i), kb + kWave * 8 * (wave + 4 * i),
+                                         16, 0, 0);
+        __builtin_amdgcn_global_load_lds(vsrc + (vcopy_off + 2048u * i), vb + kWave * 8 * (wave + 4 * i),
+                                         16, 0, 0);
+      }
+    } else {
+      // ragged last chunk: rows past the end repeat the last row (finite, and masked later)
+#pragma unroll
+      for (int i = 0; i < NCOPY; ++i) {
+        const int rr = min(crow + (256 / PPR) * i, nj - 1);
+        __builtin_amdgcn_global_load_lds(ksrc + (size_t)rr * D + 8 * kpiece,
+                                         kb + kWave * 8 * (wave + 4 * i), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(vsrc + (size_t)rr * D + 8 * vpiece,
+                                         vb + kWave * 8 * (wave + 4 * i), 16, 0, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // ---- operand addresses (elements, relative to a stage; the 32-key block enters as a constant)
+  // K operand of column step ks: row il of the block, piece 2 ks + kh
+  int koff[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) koff[ks] = il * D + 8 * ((2 * ks + kh) ^ k_piece_swizzle<D>(il));
+  // V^T operand: contraction slot e of lane half kh, step s2, is key 16 s2 + 8 (e / 4) + 4 kh +
+  // e % 4 of the block, which is where the first product left the scores in the registers.
+  // Lane i of a 16-lane group names key 4 kh + 8 half + i / 4 and the four d from
+  // 32 db + 16 (il / 16) + 4 (i % 4).
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  int voff[2][D / 32];
+  {
+    const int t = lane & 15;
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db) {
+        const int j = 4 * kh + 8 * half + (t >> 2);
+        const int d0 = 32 * db + 16 * (il >> 4) + 4 * (t & 3);
+        voff[half][db] = j * D + 8 * ((d0 >> 3) ^ (2 * (j & kVSwz))) + (d0 & 7);
+      }
+  }
+  auto vop = [&](const bf16_t* vb, int db, int jb, int s2) {
+    const int base = (32 * jb + 16 * s2) * D;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(vb + voff[0][db] + base));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(vb + voff[1][db] + base));
+    s16x8 w = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, w);
+  };
+
+  // ---- this wave's 32 query rows, as the column operand of the first product
+  u32x4 q[D / 16];
+  if (active) {
+    const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.Q) +
+                         (((size_t)b * a.Hq + h) * S + r0 + il) * D + 8 * kh;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) q[ks] = *reinterpret_cast<const u32x4*>(qrow + 16 * ks);
+  }
+
+  f32x16 acc[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  auto compute = [&](const bf16_t* kb, const bf16_t* vb, int c) {
+    if (!active) return;
+    const int nj = min(kLChunk, S - c * kLChunk);
+    int nblk = nj >> 5;
+    if (CAUSAL) nblk = min(nblk, (r0 >> 5) + 1 - 2 * c);
+    if (nblk <= 0) return;
+    const bool mask = nj < kLChunk || (CAUSAL && 2 * c + 1 >= (r0 >> 5));
+
+    f32x16 s[2];
+#pragma unroll
+    for (int jb = 0; jb < 2; ++jb) {
+      if (jb < nblk) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[jb][v] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks)
+          s[jb] = mfma_bf16(*reinterpret_cast<const bf16x8*>(kb + koff[ks] + 32 * jb * D),
+                            __builtin_bit_cast(bf16x8, q[ks]), s[jb]);
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[jb][v] = -INFINITY;
+      }
+    }
+    if (mask) {
+      const int limit = CAUSAL ? min(r0 + il, S - 1) : S - 1;   // last key this query row sees
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (c * kLChunk + 32 * jb + mfma_row(v, kh) > limit) s[jb][v] = -INFINITY;
+    }
+    float mx = fmaxf(s[0][0], s[1][0]);
+#pragma unroll
+    for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(s[0][v], s[1][v]));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx * a.scale_log2e);
+    if (__any(m_new > m_run)) {
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[db][v] *= alpha;
+      m_run = m_new;
+    }
+    float psum = 0.f;
+#pragma unroll
+    for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        s[jb][v] = __builtin_amdgcn_exp2f(fmaf(s[jb][v], a.scale_log2e, -m_new));
+        psum += s[jb][v];
+      }
+    l_run += psum;
+#pragma unroll
+    for (int jb = 0; jb < 2; ++jb) {
+      if (jb < nblk) {
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          u32x4 pw;
+          pw.x = pack_bf16(s[jb][8 * s2 + 0], s[jb][8 * s2 + 1]);
+          pw.y = pack_bf16(s[jb][8 * s2 + 2], s[jb][8 * s2 + 3]);
+          pw.z = pack_bf16(s[jb][8 * s2 + 4], s[jb][8 * s2 + 5]);
+          pw.w = pack_bf16(s[jb][8 * s2 + 6], s[jb][8 * s2 + 7]);
+          const bf16x8 pop = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db) acc[db] = mfma_bf16(vop(vb, db, jb, s2), pop, acc[db]);
+        }
+      }
+    }
+  };
+  // this wave's copies have landed (they are counted like loads), then everybody's; the
+  // barrier also retires the stage that the next copy overwrites
+  auto publish = [&]() {
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+  };
+
+  prefetch(kb0, vb0, 0);
+  for (int c = 0; c < n_chunk; c += 2) {
+    publish();
+    if (c + 1 < n_chunk) prefetch(kb1, vb1, c + 1);
+    compute(kb0, vb0, c);
+    if (c + 1 < n_chunk) {
+      publish();
+      if (c + 2 < n_chunk) prefetch(kb0, vb0, c + 2);
+      compute(kb1, vb1, c + 1);
+    }
+  }
+  __syncthreads();   // every wave is done with both stages: they now stage the output
+  if (active) {
+    const float inv = 1.0f / (l_run + __shfl_xor(l_run, 32));
+    bf16_t* Oh = reinterpret_cast<bf16_t*>(a.O) + (((size_t)b * a.Hq + h) * S + r0) * (size_t)D;
+    bf16_t* ost = wave == 0 ? kb0 : wave == 1 ? vb0 : wave == 2 ? kb1 : vb1;
+    store_tile_bf16<D>(acc, inv, ost, Oh, lane);
+  }
+}
+
 // fp32 path (vector ALUs): one wave per (batch item, head, query row).
 __global__ __launch_bounds__(kWave) void exact_f32_kernel(const ExactArgs a, int D, int causal,
                                                           float scale) {
@@ -281,6 +518,12 @@ static hipError_t launch_exact_bf16(const ExactArgs& a, dim3 grid, hipStream_t s
   return hipGetLastError();
 }
 
+template <int D, bool CAUSAL>
+static hipError_t launch_exact_long(const ExactArgs& a, dim3 grid, hipStream_t stream) {
+  hipLaunchKernelGGL((exact_bf16_long_kernel<D, CAUSAL>), grid, dim3(kThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_exact(const ExactLaunch& p, hipStream_t stream) {
   if (p.B == 0) return hipSuccess;
   ExactArgs a;
@@ -301,6 +544,13 @@ hipError_t launch_exact(const ExactLaunch& p, hipStream_t stream) {
   a.heads_per_wg = a.n_rblk == 1 ? g : 1;
   const int u8 = (a.n_kvtiles + 7) / 8 * 8;
   const dim3 grid((unsigned)((size_t)u8 * (g / a.heads_per_wg) * a.n_rblk));
+  if (a.n_rblk > 1) {   // long rows: chunked walk with direct global -> LDS copies
+    if (p.D == 64)
+      return p.causal ? launch_exact_long<64, true>(a, grid, stream)
+                      : launch_exact_long<64, false>(a, grid, stream);
+    return p.causal ? launch_exact_long<128, true>(a, grid, stream)
+                    : launch_exact_long<128, false>(a, grid, stream);
+  }
   if (p.D == 64)
     return p.causal ? launch_exact_bf16<64, true>(a, grid, stream)
                     : launch_exact_bf16<64, false>(a, grid, stream);

@@ -119,6 +119,9 @@ EXACT_CASES = [
     (2, 2, 2, 160, 64, False, 0.2, torch.bfloat16),
     (1, 3, 3, 32, 128, False, 0.0, torch.bfloat16),
     (9, 3, 1, 416, 64, True, 0.0, torch.bfloat16),
+    (1, 2, 1, 1024, 128, True, 0.0, torch.bfloat16),   # eight row blocks, up to 16 key chunks
+    (2, 2, 2, 224, 128, False, 0.0, torch.bfloat16),   # dense, ragged last chunk (32 keys)
+    (2, 4, 2, 640, 64, True, 0.15, torch.bfloat16),
 ]
 
 
