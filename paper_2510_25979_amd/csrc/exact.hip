@@ -243,6 +243,18 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 4 : 2)) void exact_bf16_kernel
 //     rescale test per 64 keys), which also gives the scheduler two independent chains.
 constexpr int kLChunk = 64;
 
+// max(x[l], x[l ^ 32]) in every lane l.  v_permlane32_swap_b32 exchanges the upper 32 lanes of
+// its first register with the lower 32 lanes of its second one, so two copies of x become
+// (lower half twice) and (upper half twice) without a trip through LDS.  Written as inline
+// assembly because the compiler builtin of the same name folds its two results into one in
+// this toolchain; the wait states around it cover the vector write -> lane permute -> vector
+// read sequence, which the compiler cannot see into.
+__device__ __forceinline__ float max_with_other_half(float x) {
+  float lo = x, hi = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(lo), "+v"(hi));
+  return fmaxf(lo, hi);
+}
+
 // permutation of the 16-byte pieces of staged K row r (unchanged by r + 256 / (D / 8))
 template <int D>
 __host__ __device__ constexpr int k_piece_swizzle(int r) {
@@ -289,22 +301,24 @@ __global__ __launch_bounds__(kThreads, 2) void exact_bf16_long_kernel(const Exac
   const int crow = slot0 / PPR, cpos = slot0 % PPR;
   const int kpiece = cpos ^ k_piece_swizzle<D>(crow);   // global piece that lands in this lane's slot
   const int vpiece = cpos ^ (2 * (crow & kVSwz));
-  const unsigned kcopy_off = (unsigned)(crow * D + 8 * kpiece);
-  const unsigned vcopy_off = (unsigned)(crow * D + 8 * vpiece);
+  // Running source pointers, one per tensor, advanced by one chunk after each use (cheaper
+  // than rebuilding 64-bit addresses from the chunk index every time).
+  const bf16_t* kptr = Ksrc + crow * D + 8 * kpiece;
+  const bf16_t* vptr = Vsrc + crow * D + 8 * vpiece;
   auto prefetch = [&](bf16_t* kb, bf16_t* vb, int c) {
     const int nj = min(kLChunk, S - c * kLChunk);
-    const bf16_t* ksrc = Ksrc + (size_t)c * kLChunk * D;
-    const bf16_t* vsrc = Vsrc + (size_t)c * kLChunk * D;
     if (nj == kLChunk) {
 #pragma unroll
       for (int i = 0; i < NCOPY; ++i) {
-        __builtin_amdgcn_global_load_lds(ksrc + (kcopy_off + 2048u * i), kb + kWave * 8 * (wave + 4 * i),
-                                         16, 0, 0);
-        __builtin_amdgcn_global_load_lds(vsrc + (vcopy_off + 2048u * i), vb + kWave * 8 * (wave + 4 * i),
-                                         16, 0, 0);
+        __builtin_amdgcn_global_load_lds(kptr + 2048 * i, kb + kWave * 8 * (wave + 4 * i), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(vptr + 2048 * i, vb + kWave * 8 * (wave + 4 * i), 16, 0, 0);
       }
+      kptr += kLChunk * D;
+      vptr += kLChunk * D;
     } else {
       // ragged last chunk: rows past the end repeat the last row (finite, and masked later)
+      const bf16_t* ksrc = Ksrc + (size_t)c * kLChunk * D;
+      const bf16_t* vsrc = Vsrc + (size_t)c * kLChunk * D;
 #pragma unroll
       for (int i = 0; i < NCOPY; ++i) {
         const int rr = min(crow + (256 / PPR) * i, nj - 1);
@@ -366,76 +380,114 @@ __global__ __launch_bounds__(kThreads, 2) void exact_bf16_long_kernel(const Exac
     for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  auto compute = [&](const bf16_t* kb, const bf16_t* vb, int c) {
+  // ---- pieces of one chunk step (32-key block jb of the stage)
+  // scores^T of block jb: 32 keys x 32 query rows, this lane: query row il, 16 of the keys
+  auto qk = [&](const bf16_t* kb, int jb) {
+    f32x16 s;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks)
+      s = mfma_bf16(*reinterpret_cast<const bf16x8*>(kb + koff[ks] + 32 * jb * D),
+                    __builtin_bit_cast(bf16x8, q[ks]), s);
+    return s;
+  };
+  // hide the keys this query row must not see (beyond the diagonal or the end of the sequence)
+  auto hide = [&](f32x16& s, int c, int jb) {
+    const int limit = (CAUSAL ? min(r0 + il, S - 1) : S - 1) - c * kLChunk - 32 * jb - 4 * kh;
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      if (8 * (v >> 2) + (v & 3) > limit) s[v] = -INFINITY;
+  };
+  // largest score of the query row: in-lane over 16 keys, then across the two lane halves
+  auto row_max = [&](const f32x16& s) {
+    float m01 = fmaxf(fmaxf(s[0], s[1]), s[2]);
+    float m02 = fmaxf(fmaxf(s[3], s[4]), s[5]);
+    float m03 = fmaxf(fmaxf(s[6], s[7]), s[8]);
+    float m04 = fmaxf(fmaxf(s[9], s[10]), s[11]);
+    float m05 = fmaxf(fmaxf(s[12], s[13]), s[14]);
+    float mx = fmaxf(fmaxf(fmaxf(m01, m02), m03), fmaxf(fmaxf(m04, m05), s[15]));
+    return max_with_other_half(mx);
+  };
+  // probabilities 2^(score * scale_log2e - m) as the packed bf16 operand of the second product;
+  // their sum is taken over the ROUNDED values (the ones that are multiplied with V), two per
+  // instruction, so numerator and denominator of the softmax see the same weights
+  typedef bf16_t bf16x2 __attribute__((ext_vector_type(2)));
+  auto probs = [&](const f32x16& s, float m, u32x4 (&pw)[2], float& sum) {
+    const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float e0 = __builtin_amdgcn_exp2f(fmaf(s[8 * s2 + 2 * w], a.scale_log2e, -m));
+        const float e1 = __builtin_amdgcn_exp2f(fmaf(s[8 * s2 + 2 * w + 1], a.scale_log2e, -m));
+        const uint32_t pk = pack_bf16(e0, e1);
+        pw[s2][w] = pk;
+        sum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, sum, false);
+      }
+  };
+  auto pv = [&](const bf16_t* vb, int jb, const u32x4 (&pw)[2]) {
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+        acc[db] = mfma_bf16(vop(vb, db, jb, s2), __builtin_bit_cast(bf16x8, pw[s2]), acc[db]);
+  };
+  auto rescale = [&](float m_new) {
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    l_run *= alpha;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[db][v] *= alpha;
+  };
+
+  // One chunk = two 32-key blocks, each with its own online-softmax step, ordered so that
+  // matrix and vector work of ONE wave can overlap (the matrix pipe runs asynchronously, but a
+  // wave issues in order): the scores of block 1 are requested before the exponentials of
+  // block 0 are taken, the second product of block 0 before the exponentials of block 1.
+  // The accumulator is rescaled only when some row maximum moved; for block 1 that happens
+  // after the second product of block 0 has been added (its weights refer to the old maximum).
+  // MASKED is the variant for chunks that touch the diagonal or the ragged end (nblk of the
+  // two blocks exist for this wave, some of their keys may be hidden); the other variant has no
+  // per-element tests.  The flag is a literal at every call site and the body is inlined.
+  auto step = [&](const bf16_t* kb, const bf16_t* vb, int c, int nblk, const bool MASKED)
+      __attribute__((always_inline)) {
+    const bool two = !MASKED || nblk > 1;
+    f32x16 s0 = qk(kb, 0);
+    if (MASKED) hide(s0, c, 0);
+    const float m0 = fmaxf(m_run, row_max(s0) * a.scale_log2e);
+    if (__any(m0 > m_run)) rescale(m0);
+    m_run = m0;
+    f32x16 s1;
+    if (two) s1 = qk(kb, 1);
+    u32x4 p0[2];
+    float sum0 = 0.f;
+    probs(s0, m0, p0, sum0);
+    l_run += sum0;
+    if (two) {
+      if (MASKED) hide(s1, c, 1);
+      const float m1 = fmaxf(m0, row_max(s1) * a.scale_log2e);
+      const bool moved = __any(m1 > m0);
+      pv(vb, 0, p0);
+      u32x4 p1[2];
+      float sum1 = 0.f;
+      probs(s1, m1, p1, sum1);
+      if (moved) rescale(m1);
+      m_run = m1;
+      l_run += sum1;
+      pv(vb, 1, p1);
+    } else {
+      pv(vb, 0, p0);
+    }
+  };
+  // chunk c through the masked variant (exact for every chunk, only slower)
+  auto tail_step = [&](const bf16_t* kb, const bf16_t* vb, int c) {
     if (!active) return;
     const int nj = min(kLChunk, S - c * kLChunk);
     int nblk = nj >> 5;
     if (CAUSAL) nblk = min(nblk, (r0 >> 5) + 1 - 2 * c);
-    if (nblk <= 0) return;
-    const bool mask = nj < kLChunk || (CAUSAL && 2 * c + 1 >= (r0 >> 5));
-
-    f32x16 s[2];
-#pragma unroll
-    for (int jb = 0; jb < 2; ++jb) {
-      if (jb < nblk) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s[jb][v] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks)
-          s[jb] = mfma_bf16(*reinterpret_cast<const bf16x8*>(kb + koff[ks] + 32 * jb * D),
-                            __builtin_bit_cast(bf16x8, q[ks]), s[jb]);
-      } else {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s[jb][v] = -INFINITY;
-      }
-    }
-    if (mask) {
-      const int limit = CAUSAL ? min(r0 + il, S - 1) : S - 1;   // last key this query row sees
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          if (c * kLChunk + 32 * jb + mfma_row(v, kh) > limit) s[jb][v] = -INFINITY;
-    }
-    float mx = fmaxf(s[0][0], s[1][0]);
-#pragma unroll
-    for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(s[0][v], s[1][v]));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx * a.scale_log2e);
-    if (__any(m_new > m_run)) {
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      l_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[db][v] *= alpha;
-      m_run = m_new;
-    }
-    float psum = 0.f;
-#pragma unroll
-    for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        s[jb][v] = __builtin_amdgcn_exp2f(fmaf(s[jb][v], a.scale_log2e, -m_new));
-        psum += s[jb][v];
-      }
-    l_run += psum;
-#pragma unroll
-    for (int jb = 0; jb < 2; ++jb) {
-      if (jb < nblk) {
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          u32x4 pw;
-          pw.x = pack_bf16(s[jb][8 * s2 + 0], s[jb][8 * s2 + 1]);
-          pw.y = pack_bf16(s[jb][8 * s2 + 2], s[jb][8 * s2 + 3]);
-          pw.z = pack_bf16(s[jb][8 * s2 + 4], s[jb][8 * s2 + 5]);
-          pw.w = pack_bf16(s[jb][8 * s2 + 6], s[jb][8 * s2 + 7]);
-          const bf16x8 pop = __builtin_bit_cast(bf16x8, pw);
-#pragma unroll
-          for (int db = 0; db < D / 32; ++db) acc[db] = mfma_bf16(vop(vb, db, jb, s2), pop, acc[db]);
-        }
-      }
-    }
+    if (nblk > 0) step(kb, vb, c, nblk, true);
   };
   // this wave's copies have landed (they are counted like loads), then everybody's; the
   // barrier also retires the stage that the next copy overwrites
@@ -444,16 +496,29 @@ __global__ __launch_bounds__(kThreads, 2) void exact_bf16_long_kernel(const Exac
     __syncthreads();
   };
 
+  // Chunks below c_split are complete and fully visible to every wave of the workgroup (they
+  // lie left of the diagonal blocks of all 128 rows, and before a ragged end): the main loop
+  // runs only the test-free variant, two chunks per trip so that stages alternate without
+  // pointer arithmetic.  The few chunks from c_split on go through the masked variant.
+  const int c_split = CAUSAL ? min(2 * R, S / kLChunk) : S / kLChunk;
   prefetch(kb0, vb0, 0);
-  for (int c = 0; c < n_chunk; c += 2) {
+  int c = 0;
+  for (; c + 1 < c_split; c += 2) {
     publish();
-    if (c + 1 < n_chunk) prefetch(kb1, vb1, c + 1);
-    compute(kb0, vb0, c);
-    if (c + 1 < n_chunk) {
-      publish();
-      if (c + 2 < n_chunk) prefetch(kb0, vb0, c + 2);
-      compute(kb1, vb1, c + 1);
-    }
+    prefetch(kb1, vb1, c + 1);
+    if (active) step(kb0, vb0, c, 2, false);
+    publish();
+    if (c + 2 < n_chunk) prefetch(kb0, vb0, c + 2);
+    if (active) step(kb1, vb1, c + 1, 2, false);
+  }
+  // (one copy of the masked code: the stage is picked at run time, which only costs the
+  // compiler its proof that copy and reads touch different arrays, i.e. some overlap)
+  for (; c < n_chunk; ++c) {
+    publish();
+    bf16_t* kcur = (c & 1) ? kb1 : kb0;
+    bf16_t* vcur = (c & 1) ? vb1 : vb0;
+    if (c + 1 < n_chunk) prefetch((c & 1) ? kb0 : kb1, (c & 1) ? vb0 : vb1, c + 1);
+    tail_step(kcur, vcur, c);
   }
   __syncthreads();   // every wave is done with both stages: they now stage the output
   if (active) {
