@@ -242,6 +242,7 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 4 : 2)) void exact_bf16_kernel
 //   * the two 32-key blocks of a chunk share one softmax step (one maximum exchange, one
 //     rescale test per 64 keys), which also gives the scheduler two independent chains.
 constexpr int kLChunk = 64;
+constexpr float kRescaleSlack = 8.0f;   // log2 units
 
 // max(x[l], x[l ^ 32]) in every lane l.  v_permlane32_swap_b32 exchanges the upper 32 lanes of
 // its first register with the lower 32 lanes of its second one, so two copies of x become
@@ -446,8 +447,13 @@ __global__ __launch_bounds__(kThreads, 2) void exact_bf16_long_kernel(const Exac
   // matrix and vector work of ONE wave can overlap (the matrix pipe runs asynchronously, but a
   // wave issues in order): the scores of block 1 are requested before the exponentials of
   // block 0 are taken, the second product of block 0 before the exponentials of block 1.
-  // The accumulator is rescaled only when some row maximum moved; for block 1 that happens
-  // after the second product of block 0 has been added (its weights refer to the old maximum).
+  // The reference point m of a row (weights are 2^(score - m)) follows the row maximum lazily:
+  // it moves, and the accumulator is rescaled, only when some row of the wave has outgrown
+  // its reference by more than kRescaleSlack, so weights stay below 2^kRescaleSlack and almost
+  // every step skips the rescaling (a new maximum turns up in nearly every block of random
+  // scores, a jump by 2^8 hardly ever); the final division by the row sum makes the result
+  // independent of m.  For block 1 the rescaling happens after the second product of block 0
+  // has been added (those weights refer to the old m).
   // MASKED is the variant for chunks that touch the diagonal or the ragged end (nblk of the
   // two blocks exist for this wave, some of their keys may be hidden); the other variant has no
   // per-element tests.  The flag is a literal at every call site and the body is inlined.
@@ -456,8 +462,14 @@ __global__ __launch_bounds__(kThreads, 2) void exact_bf16_long_kernel(const Exac
     const bool two = !MASKED || nblk > 1;
     f32x16 s0 = qk(kb, 0);
     if (MASKED) hide(s0, c, 0);
-    const float m0 = fmaxf(m_run, row_max(s0) * a.scale_log2e);
-    if (__any(m0 > m_run)) rescale(m0);
+    float m0 = m_run;
+    {
+      const float cand = fmaxf(m_run, row_max(s0) * a.scale_log2e);
+      if (__any(cand > m_run + kRescaleSlack)) {
+        rescale(cand);
+        m0 = cand;
+      }
+    }
     m_run = m0;
     f32x16 s1;
     if (two) s1 = qk(kb, 1);
@@ -467,8 +479,9 @@ __global__ __launch_bounds__(kThreads, 2) void exact_bf16_long_kernel(const Exac
     l_run += sum0;
     if (two) {
       if (MASKED) hide(s1, c, 1);
-      const float m1 = fmaxf(m0, row_max(s1) * a.scale_log2e);
-      const bool moved = __any(m1 > m0);
+      const float cand1 = fmaxf(m0, row_max(s1) * a.scale_log2e);
+      const bool moved = __any(cand1 > m0 + kRescaleSlack);
+      const float m1 = moved ? cand1 : m0;
       pv(vb, 0, p0);
       u32x4 p1[2];
       float sum1 = 0.f;
