@@ -20,7 +20,7 @@
 // rotated with the workgroup and head index so that all four SIMDs see the
 // same mix.  K is staged row-major, V transposed, 128 keys per LDS chunk.
 // Softmax runs in the log2 domain with the scale folded into one FMA per
-// score; the accumulator is rescaled only when some row maximum moved.
+// score; the accumulator is rescaled only when some row maximum has moved far.
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -29,6 +29,9 @@ namespace ac {
 constexpr int kKPad = 8;   // elements of padding per staged K row (keeps 16-byte alignment)
 constexpr int kOPass = 64; // output columns staged per pass (16 rows at a time)
 constexpr int kOStride = kOPass + 4;
+// Online softmax: weights are 2^(score - m); m moves (and the accumulator is rescaled) only when
+// a row maximum has outgrown it by more than this many bits, see the long-sequence kernel.
+constexpr float kRescaleSlack = 8.0f;
 
 
 struct ExactArgs {
@@ -39,6 +42,7 @@ struct ExactArgs {
   int32_t heads_per_wg;
   int32_t n_rblk;
   int32_t n_kvtiles;
+  int32_t n_blocks;   // tiles of the short-sequence kernel (its grid may be smaller)
   float scale_log2e;
 };
 
@@ -54,174 +58,184 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 4 : 2)) void exact_bf16_kernel
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
   const int il = lane & 31, kh = lane >> 5;
   const int S = a.S, g = a.Hq / a.Hkv;
-  const int bid = blockIdx.x;
-  const int slot = bid >> 3;
-  const int hslots = g / a.heads_per_wg;
-  const int per_u = hslots * a.n_rblk;
-  const int u = (slot / per_u) * 8 + (bid & 7);
-  if (u >= a.n_kvtiles) return;
-  const int h_first = ((slot % per_u) / a.n_rblk) * a.heads_per_wg;
-  const int R = a.n_rblk - 1 - (slot % per_u) % a.n_rblk;
-  const int b = u / a.Hkv, kvh = u % a.Hkv;
-  if (a.row_sel && a.row_sel[b] >= 0) return;
+  // One tile per workgroup, or (when queries are routed, so that many tiles may have nothing
+  // to do) a fixed number of workgroups that each take every gridDim.x-th tile: skipping a
+  // tile then costs a scalar test instead of a workgroup launch.
+  bool first_tile = true;
+  for (int bid = blockIdx.x; bid < a.n_blocks; bid += gridDim.x) {
+    const int slot = bid >> 3;
+    const int hslots = g / a.heads_per_wg;
+    const int per_u = hslots * a.n_rblk;
+    const int u = (slot / per_u) * 8 + (bid & 7);
+    if (u >= a.n_kvtiles) continue;
+    const int h_first = ((slot % per_u) / a.n_rblk) * a.heads_per_wg;
+    const int R = a.n_rblk - 1 - (slot % per_u) % a.n_rblk;
+    const int b = u / a.Hkv, kvh = u % a.Hkv;
+    if (a.row_sel && a.row_sel[b] >= 0) continue;
+    if (!first_tile) __syncthreads();   // the previous tile's output staging used the same LDS
+    first_tile = false;
 
-  const bf16_t* Kt = reinterpret_cast<const bf16_t*>(a.K) + (size_t)u * S * D;
-  const bf16_t* Vt_src = reinterpret_cast<const bf16_t*>(a.V) + (size_t)u * S * D;
-  const int n_chunk = CAUSAL ? R + 1 : (S + kChunk - 1) / kChunk;
-  const int nrow32 = min(4, (S - R * kChunk) >> 5);
-  const int rot = slot & 3;
+    const bf16_t* Kt = reinterpret_cast<const bf16_t*>(a.K) + (size_t)u * S * D;
+    const bf16_t* Vt_src = reinterpret_cast<const bf16_t*>(a.V) + (size_t)u * S * D;
+    const int n_chunk = CAUSAL ? R + 1 : (S + kChunk - 1) / kChunk;
+    const int nrow32 = min(4, (S - R * kChunk) >> 5);
+    const int rot = slot & 3;
 
-  auto load_q = [&](int hl, u32x4 (&q)[D / 16]) {
-    const int rw = (wave + rot + hl) & 3;
-    if (rw < nrow32) {
-      const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.Q) +
-                           (((size_t)b * a.Hq + kvh * g + h_first + hl) * S + R * kChunk + 32 * rw + il) * D +
-                           8 * kh;
+    auto load_q = [&](int hl, u32x4 (&q)[D / 16]) {
+      const int rw = (wave + rot + hl) & 3;
+      if (rw < nrow32) {
+        const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.Q) +
+                             (((size_t)b * a.Hq + kvh * g + h_first + hl) * S + R * kChunk + 32 * rw + il) * D +
+                             8 * kh;
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) q[ks] = *reinterpret_cast<const u32x4*>(qrow + 16 * ks);
-    }
-  };
-
-  u32x4 qreg[D / 16], qnext[D / 16];
-  load_q(0, qnext);
-
-  for (int hl = 0; hl < a.heads_per_wg; ++hl) {
-    const int h = kvh * g + h_first + hl;
-    const int rw = (wave + rot + hl) & 3;
-    const bool active = rw < nrow32;
-    const int r0 = R * kChunk + 32 * rw;
-#pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) qreg[ks] = qnext[ks];
-
-    f32x16 acc[D / 32];
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
-    float m_run = -INFINITY;
-    float l_run = 0.f;
-
-    for (int c = 0; c < n_chunk; ++c) {
-      const int j0 = c * kChunk;
-      const int nj = min(kChunk, S - j0);
-      if (hl == 0 || n_chunk > 1) {
-        if (c > 0 || hl > 0) __syncthreads();
-        constexpr int DQ = D / 8;
-        const u32x4* src = reinterpret_cast<const u32x4*>(Kt + (size_t)j0 * D);
-        for (int p = tid; p < nj * DQ; p += kThreads) {
-          const int j = p / DQ, dq = p % DQ;
-          *reinterpret_cast<u32x4*>(ks_lds + j * KS + 8 * dq) = src[p];
-        }
-        stage_v_transposed<D>(Vt_src + (size_t)j0 * D, nj, vt, tid);
-        __syncthreads();
+        for (int ks = 0; ks < D / 16; ++ks) q[ks] = *reinterpret_cast<const u32x4*>(qrow + 16 * ks);
       }
-      if (c + 1 == n_chunk && hl + 1 < a.heads_per_wg) load_q(hl + 1, qnext);
+    };
 
+    u32x4 qreg[D / 16], qnext[D / 16];
+    load_q(0, qnext);
+
+    for (int hl = 0; hl < a.heads_per_wg; ++hl) {
+      const int h = kvh * g + h_first + hl;
+      const int rw = (wave + rot + hl) & 3;
+      const bool active = rw < nrow32;
+      const int r0 = R * kChunk + 32 * rw;
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) qreg[ks] = qnext[ks];
+
+      f32x16 acc[D / 32];
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+      float m_run = -INFINITY;
+      float l_run = 0.f;
+
+      for (int c = 0; c < n_chunk; ++c) {
+        const int j0 = c * kChunk;
+        const int nj = min(kChunk, S - j0);
+        if (hl == 0 || n_chunk > 1) {
+          if (c > 0 || hl > 0) __syncthreads();
+          constexpr int DQ = D / 8;
+          const u32x4* src = reinterpret_cast<const u32x4*>(Kt + (size_t)j0 * D);
+          for (int p = tid; p < nj * DQ; p += kThreads) {
+            const int j = p / DQ, dq = p % DQ;
+            *reinterpret_cast<u32x4*>(ks_lds + j * KS + 8 * dq) = src[p];
+          }
+          stage_v_transposed<D>(Vt_src + (size_t)j0 * D, nj, vt, tid);
+          __syncthreads();
+        }
+        if (c + 1 == n_chunk && hl + 1 < a.heads_per_wg) load_q(hl + 1, qnext);
+
+        if (active) {
+          int nblk = nj >> 5;
+          if (CAUSAL) nblk = min(nblk, (r0 - j0) / 32 + 1);
+          int jb = 0;
+          for (; jb < nblk; ++jb) {
+            f32x16 s;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s[v] = 0.f;
+            const bf16_t* krow = ks_lds + (32 * jb + il) * KS + 8 * kh;
+#pragma unroll
+            for (int ks = 0; ks < D / 16; ++ks)
+              s = mfma_bf16(*reinterpret_cast<const bf16x8*>(krow + 16 * ks),
+                            __builtin_bit_cast(bf16x8, qreg[ks]), s);
+            if (CAUSAL && j0 + 32 * jb == r0) {
+#pragma unroll
+              for (int v = 0; v < 16; ++v)
+                if (mfma_row(v, kh) > il) s[v] = -INFINITY;
+            }
+            float mx = s[0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            // the reference point follows the row maximum with kRescaleSlack bits of slack
+            float m_new = m_run;
+            {
+              const float cand = fmaxf(m_run, mx * a.scale_log2e);
+              if (__any(cand > m_run + kRescaleSlack)) {
+                const float alpha = __builtin_amdgcn_exp2f(m_run - cand);
+                l_run *= alpha;
+#pragma unroll
+                for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                  for (int v = 0; v < 16; ++v) acc[db][v] *= alpha;
+                m_run = m_new = cand;
+              }
+            }
+            float psum = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              s[v] = __builtin_amdgcn_exp2f(fmaf(s[v], a.scale_log2e, -m_new));
+              psum += s[v];
+            }
+            l_run += psum;
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+              u32x4 pw;
+              pw.x = pack_bf16(s[8 * s2 + 0], s[8 * s2 + 1]);
+              pw.y = pack_bf16(s[8 * s2 + 2], s[8 * s2 + 3]);
+              pw.z = pack_bf16(s[8 * s2 + 4], s[8 * s2 + 5]);
+              pw.w = pack_bf16(s[8 * s2 + 6], s[8 * s2 + 7]);
+              const bf16x8 pop = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+              for (int db = 0; db < D / 32; ++db) {
+                const bf16_t* vrow = vt + (32 * db + il) * kVtStride + 32 * jb + 16 * s2 + 4 * kh;
+                u32x2 lo = *reinterpret_cast<const u32x2*>(vrow);
+                u32x2 hi = *reinterpret_cast<const u32x2*>(vrow + 8);
+                u32x4 w = {lo.x, lo.y, hi.x, hi.y};
+                acc[db] = mfma_bf16(__builtin_bit_cast(bf16x8, w), pop, acc[db]);
+              }
+            }
+          }
+        }
+      }
+
+      if (a.heads_per_wg == 1) __syncthreads();
       if (active) {
-        int nblk = nj >> 5;
-        if (CAUSAL) nblk = min(nblk, (r0 - j0) / 32 + 1);
-        int jb = 0;
-        for (; jb < nblk; ++jb) {
-          f32x16 s;
+        const float inv = 1.0f / (l_run + __shfl_xor(l_run, 32));
+        bf16_t* Oh = reinterpret_cast<bf16_t*>(a.O) + (((size_t)b * a.Hq + h) * S + r0) * (size_t)D;
+        if (a.heads_per_wg == 1) {
+          // K is no longer needed: the whole 32 x D tile is staged on top of it and leaves as
+          // complete contiguous rows (measurably better than 64-byte row segments)
+          store_tile_bf16<D>(acc, inv, ks_lds + wave * (32 * (D + 4)), Oh, lane);
+        } else {
+          // K must survive for the next head: a small wave-private buffer takes 16 rows x 64
+          // columns per pass, so every global store still covers whole 128-byte lines
+          bf16_t* ost = ost_all + wave * (16 * kOStride);
 #pragma unroll
-          for (int v = 0; v < 16; ++v) s[v] = 0.f;
-          const bf16_t* krow = ks_lds + (32 * jb + il) * KS + 8 * kh;
+          for (int rh = 0; rh < 2; ++rh)
 #pragma unroll
-          for (int ks = 0; ks < D / 16; ++ks)
-            s = mfma_bf16(*reinterpret_cast<const bf16x8*>(krow + 16 * ks),
-                          __builtin_bit_cast(bf16x8, qreg[ks]), s);
-          if (CAUSAL && j0 + 32 * jb == r0) {
+            for (int dh = 0; dh < D / 64; ++dh) {
+              if ((il >> 4) == rh) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v)
-              if (mfma_row(v, kh) > il) s[v] = -INFINITY;
-          }
-          float mx = s[0];
+                for (int dbp = 0; dbp < 2; ++dbp)
 #pragma unroll
-          for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
-          mx = fmaxf(mx, __shfl_xor(mx, 32));
-          const float m_new = fmaxf(m_run, mx * a.scale_log2e);
-          if (__any(m_new > m_run))
-          {
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            l_run *= alpha;
+                  for (int vq = 0; vq < 4; ++vq) {
+                    const f32x16& t = acc[2 * dh + dbp];
+                    u32x2 w;
+                    w.x = pack_bf16(t[4 * vq] * inv, t[4 * vq + 1] * inv);
+                    w.y = pack_bf16(t[4 * vq + 2] * inv, t[4 * vq + 3] * inv);
+                    *reinterpret_cast<u32x2*>(ost + (il & 15) * kOStride + 32 * dbp + 8 * vq + 4 * kh) = w;
+                  }
+              }
+              __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+              __builtin_amdgcn_wave_barrier();
+              __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-            for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-              for (int v = 0; v < 16; ++v) acc[db][v] *= alpha;
-            m_run = m_new;
-          }
-          float psum = 0.f;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            s[v] = __builtin_amdgcn_exp2f(fmaf(s[v], a.scale_log2e, -m_new));
-            psum += s[v];
-          }
-          l_run += psum;
-#pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2) {
-            u32x4 pw;
-            pw.x = pack_bf16(s[8 * s2 + 0], s[8 * s2 + 1]);
-            pw.y = pack_bf16(s[8 * s2 + 2], s[8 * s2 + 3]);
-            pw.z = pack_bf16(s[8 * s2 + 4], s[8 * s2 + 5]);
-            pw.w = pack_bf16(s[8 * s2 + 6], s[8 * s2 + 7]);
-            const bf16x8 pop = __builtin_bit_cast(bf16x8, pw);
-#pragma unroll
-            for (int db = 0; db < D / 32; ++db) {
-              const bf16_t* vrow = vt + (32 * db + il) * kVtStride + 32 * jb + 16 * s2 + 4 * kh;
-              u32x2 lo = *reinterpret_cast<const u32x2*>(vrow);
-              u32x2 hi = *reinterpret_cast<const u32x2*>(vrow + 8);
-              u32x4 w = {lo.x, lo.y, hi.x, hi.y};
-              acc[db] = mfma_bf16(__builtin_bit_cast(bf16x8, w), pop, acc[db]);
+              for (int it = 0; it < 2; ++it) {
+                const int p = it * kWave + lane;
+                const int row = p >> 3, c8 = p & 7;
+                const u32x2* sp = reinterpret_cast<const u32x2*>(ost + row * kOStride + 8 * c8);
+                u32x2 lo = sp[0], hi = sp[1];
+                __builtin_nontemporal_store(
+                    u32x4{lo.x, lo.y, hi.x, hi.y},
+                    reinterpret_cast<u32x4*>(Oh + (size_t)(16 * rh + row) * D + 64 * dh + 8 * c8));
+              }
+              __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+              __builtin_amdgcn_wave_barrier();
             }
-          }
         }
-      }
-    }
-
-    if (a.heads_per_wg == 1) __syncthreads();
-    if (active) {
-      const float inv = 1.0f / (l_run + __shfl_xor(l_run, 32));
-      bf16_t* Oh = reinterpret_cast<bf16_t*>(a.O) + (((size_t)b * a.Hq + h) * S + r0) * (size_t)D;
-      if (a.heads_per_wg == 1) {
-        // K is no longer needed: the whole 32 x D tile is staged on top of it and leaves as
-        // complete contiguous rows (measurably better than 64-byte row segments)
-        store_tile_bf16<D>(acc, inv, ks_lds + wave * (32 * (D + 4)), Oh, lane);
-      } else {
-        // K must survive for the next head: a small wave-private buffer takes 16 rows x 64
-        // columns per pass, so every global store still covers whole 128-byte lines
-        bf16_t* ost = ost_all + wave * (16 * kOStride);
-#pragma unroll
-        for (int rh = 0; rh < 2; ++rh)
-#pragma unroll
-          for (int dh = 0; dh < D / 64; ++dh) {
-            if ((il >> 4) == rh) {
-#pragma unroll
-              for (int dbp = 0; dbp < 2; ++dbp)
-#pragma unroll
-                for (int vq = 0; vq < 4; ++vq) {
-                  const f32x16& t = acc[2 * dh + dbp];
-                  u32x2 w;
-                  w.x = pack_bf16(t[4 * vq] * inv, t[4 * vq + 1] * inv);
-                  w.y = pack_bf16(t[4 * vq + 2] * inv, t[4 * vq + 3] * inv);
-                  *reinterpret_cast<u32x2*>(ost + (il & 15) * kOStride + 32 * dbp + 8 * vq + 4 * kh) = w;
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-            for (int it = 0; it < 2; ++it) {
-              const int p = it * kWave + lane;
-              const int row = p >> 3, c8 = p & 7;
-              const u32x2* sp = reinterpret_cast<const u32x2*>(ost + row * kOStride + 8 * c8);
-              u32x2 lo = sp[0], hi = sp[1];
-              __builtin_nontemporal_store(
-                  u32x4{lo.x, lo.y, hi.x, hi.y},
-                  reinterpret_cast<u32x4*>(Oh + (size_t)(16 * rh + row) * D + 64 * dh + 8 * c8));
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-          }
       }
     }
   }
@@ -242,7 +256,6 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 4 : 2)) void exact_bf16_kernel
 //   * the two 32-key blocks of a chunk share one softmax step (one maximum exchange, one
 //     rescale test per 64 keys), which also gives the scheduler two independent chains.
 constexpr int kLChunk = 64;
-constexpr float kRescaleSlack = 8.0f;   // log2 units
 
 // max(x[l], x[l ^ 32]) in every lane l.  v_permlane32_swap_b32 exchanges the upper 32 lanes of
 // its first register with the lower 32 lanes of its second one, so two copies of x become
@@ -588,7 +601,11 @@ static size_t exact_lds_bytes(int D, int heads_per_wg) {
 }
 
 template <int D, bool CAUSAL>
-static hipError_t launch_exact_bf16(const ExactArgs& a, dim3 grid, hipStream_t stream) {
+static hipError_t launch_exact_bf16(ExactArgs a, dim3 grid, hipStream_t stream) {
+  a.n_blocks = (int32_t)grid.x;
+  // routed launch: 8 workgroups per compute unit walk the tiles (a multiple of 8 keeps the
+  // tile -> XCD assignment of the one-tile-per-workgroup launch)
+  if (a.row_sel && grid.x > 2048u) grid.x = 2048u;
   const size_t lds = exact_lds_bytes(D, a.heads_per_wg);
   hipError_t e = ensure_lds<&exact_bf16_kernel<D, CAUSAL>>(lds);
   if (e != hipSuccess) return e;

@@ -291,6 +291,65 @@ def test_search_map_of_and_threshold(ac, oracle_mod):
 
 # ------------------------------------------------------------------ error paths
 
+def test_whole_step_replayed_from_a_hip_graph_matches_eager(ac, oracle_mod):
+    # search -> reuse -> exact on the misses, captured once into a HIP graph and replayed with
+    # new inputs written into the same buffers; every replay must equal the eager result, with
+    # eager work and synchronisations of the program's own between the replays
+    B, M, L, Hq, Hkv, S, D, E = 8, 64, 2, 4, 2, 128, 64, 64
+    g = _gen(77)
+    maps = _maps(M, L, Hq, S, torch.bfloat16, True, 78)
+    emb = torch.nn.functional.normalize(torch.randn(M, E, generator=g), dim=-1).half()
+    db = _build(ac, emb, maps, "packed", True, n_kv_heads=Hkv, head_dim=D)
+    dev = torch.device("cuda")
+    q = torch.empty(B, E, dtype=torch.float16, device=dev)
+    Q = torch.empty(B, L * Hq, S, D, dtype=torch.bfloat16, device=dev)
+    K = torch.empty(B, L * Hkv, S, D, dtype=torch.bfloat16, device=dev)
+    V = torch.empty(B, L * Hkv, S, D, dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(ac.attncache_workspace_bytes(db.desc, B, 1), dtype=torch.uint8, device=dev)
+    idx = torch.empty(B, 1, dtype=torch.int32, device=dev)
+    score = torch.empty(B, 1, dtype=torch.float32, device=dev)
+    hit = torch.empty(B, dtype=torch.int32, device=dev)
+    O = torch.empty(B, L * Hq, S, D, dtype=torch.bfloat16, device=dev)
+
+    def step(out):
+        ac.attncache_search(db, q, 1, 0.8, idx, score, hit, ws)
+        ac.attncache_apply(db, hit, V.view(B, L, Hkv, S, D), out.view(B, L, Hq, S, D))
+        ac.attention_exact(Q, K, V, out, causal=True, row_sel=hit)
+
+    def new_inputs(seed):
+        gg = _gen(seed)
+        rows = torch.randint(0, M, (B,), generator=gg)
+        qq = emb[rows].float() + 0.02 * torch.randn(B, E, generator=gg)
+        qq[::3] = torch.randn(B, E, generator=gg)[::3]            # every third query misses
+        q.copy_(torch.nn.functional.normalize(qq, dim=-1).half())
+        for t in (Q, K, V):
+            t.copy_(torch.randn(t.shape, generator=gg).to(torch.bfloat16))
+
+    new_inputs(1)
+    step(O)                                                       # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(O)
+    torch.cuda.synchronize()
+    for seed in (2, 3, 4):
+        new_inputs(seed)
+        O.fill_(5.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        got, got_hit = O.clone(), hit.clone()
+        eager = torch.full_like(O, 5.0)
+        step(eager)
+        torch.cuda.synchronize()
+        assert torch.equal(got_hit, hit)
+        assert (hit >= 0).any() and (hit < 0).any()
+        assert torch.equal(got, eager), seed
+    db.close()
+
+
 def test_error_codes(ac):
     emb = torch.zeros(64, 128, dtype=torch.float16, device="cuda")
     maps = torch.zeros(64, 1, 2, 32, 32, dtype=torch.bfloat16, device="cuda")
