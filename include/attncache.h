@@ -17,7 +17,9 @@
  *   - The library never allocates or frees device memory.  Inputs, outputs,
  *     workspace and staging memory are owned by the caller; a database
  *     handle borrows the pointers it is given and the caller keeps that
- *     memory alive and unmodified until attncache_destroy_db().
+ *     memory alive until attncache_destroy_db() and does not modify it
+ *     behind the library's back (attncache_insert is the library's own
+ *     way of writing it).
  *   - Tensors are dense, row-major, innermost index last, no padding.
  *     Every tensor base pointer must be 16-byte aligned.
  *   - Notation: B queries, N database feature vectors of dimension E,
@@ -231,6 +233,50 @@ int32_t attention_exact(const void *Q, const void *K, const void *V, void *O,
                         const int32_t *row_sel, int32_t B, int32_t Hq,
                         int32_t Hkv, int32_t S, int32_t D, int32_t dtype,
                         int32_t causal, float scale, void *stream);
+
+/*
+ * Database building on the device (Fig. 3, steps 2 and 3: the attention maps
+ * an input produced are stored under the input's feature vector): the
+ * recompute branch for items that are to be remembered.  For every item b
+ * with row_sel[b] < 0 (or row_sel == NULL)
+ *
+ *   O[b][l][h]                            = softmax(scale * Q K^T) V   (as attention_exact)
+ *   maps[slot[b]][layer_begin + l][h]     = softmax(scale * Q K^T), rounded
+ *                                           once to bf16, in the database's
+ *                                           map layout (dense causal maps get
+ *                                           their zeros above the diagonal)
+ *   emb[slot[b]]                          = feat[b]
+ *
+ * for l in [0, layer_count), so that a later attncache_search hit on the slot
+ * makes attncache_apply reproduce O from the stored map.  O is formed from
+ * the ROUNDED map (what the reuse branch will read), fp32 accumulation.
+ *
+ *   db        map_dtype AC_BF16, maps in DEVICE memory (AC_ERR_DTYPE /
+ *             AC_ERR_MEMSPACE otherwise).  This is the one entry point that
+ *             WRITES the memory the handle borrows (feature rows and map
+ *             entries of the named slots); the caller orders it against
+ *             searches and reuses of the same slots (same stream, or events).
+ *   feat      DEVICE [B][E] of emb_dtype, or NULL to store maps only (a
+ *             layer-by-layer caller passes it once).  Requires map_of == NULL
+ *             and N == M (one index for both stores) and E * sizeof(element)
+ *             a multiple of 16.
+ *   slot      DEVICE [B] int32: entry to overwrite, values outside [0, M)
+ *             (e.g. -1) store nothing for that item.  NULL: nothing is stored
+ *             at all.  Slots of one call must be distinct (equal slots race).
+ *   row_sel   NULL or DEVICE [B] int32: items with row_sel[b] >= 0 are skipped
+ *             entirely (pass the hit array to handle only the misses).
+ *   Q         DEVICE [B][layer_count][Hq][S][D] bf16; K, V DEVICE
+ *             [B][layer_count][Hkv][S][D]; O DEVICE like Q.
+ *   scale     0 selects 1/sqrt(D).
+ *
+ * Two passes over the keys (row statistics first, then the normalised
+ * weights), so it costs about twice the first product of attention_exact.
+ */
+int32_t attncache_insert(attncache_db *db, const void *feat,
+                         const int32_t *slot, const int32_t *row_sel,
+                         const void *Q, const void *K, const void *V, void *O,
+                         int32_t B, int32_t layer_begin, int32_t layer_count,
+                         float scale, void *stream);
 
 /* Short constant description of a status code. */
 const char *attncache_status_string(int32_t status);

@@ -26,7 +26,8 @@ _DTYPE_CODE = {torch.float32: AC_F32, torch.float16: AC_F16, torch.bfloat16: AC_
 
 SYMBOLS = ["attncache_workspace_bytes", "attncache_map_entry_bytes", "attncache_pack_maps",
            "attncache_build_db", "attncache_destroy_db",
-           "attncache_search", "attncache_apply", "attention_exact", "attncache_status_string",
+           "attncache_search", "attncache_apply", "attention_exact", "attncache_insert",
+           "attncache_status_string",
            "attncache_last_hip_error", "attncache_version"]
 
 
@@ -78,6 +79,8 @@ def lib():
         L.attncache_apply.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
         L.attention_exact.restype = i32
         L.attention_exact.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, f32, vp]
+        L.attncache_insert.restype = i32
+        L.attncache_insert.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp]
         L.attncache_status_string.restype = ctypes.c_char_p
         L.attncache_status_string.argtypes = [i32]
         L.attncache_last_hip_error.restype = i32
@@ -247,6 +250,28 @@ def attncache_apply(db: Database, hit: torch.Tensor, V: torch.Tensor, O: torch.T
         hp = _dev(hit, "hit", torch.int32, (B,))
     _check(lib().attncache_apply(db.handle, hp, vp, op, B, layer_begin, Lc, _stream(stream)),
            "attncache_apply")
+
+
+def attncache_insert(db: Database, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, O: torch.Tensor, *,
+                     slot: Optional[torch.Tensor] = None, feat: Optional[torch.Tensor] = None,
+                     row_sel: Optional[torch.Tensor] = None, layer_begin: int = 0,
+                     scale: float = 0.0, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Q,O [B,Lc,Hq,S,D]; K,V [B,Lc,Hkv,S,D] bf16; slot, row_sel [B] int32; feat [B,E]."""
+    d = db.desc
+    if Q.dim() != 5:
+        raise ValueError("Q must be [B,Lc,Hq,S,D]")
+    B, Lc = Q.shape[0], Q.shape[1]
+    dt = torch.bfloat16
+    qp = _dev(Q, "Q", dt, (B, Lc, d.n_q_heads, d.seq_len, d.head_dim))
+    kp = _dev(K, "K", dt, (B, Lc, d.n_kv_heads, d.seq_len, d.head_dim))
+    vp = _dev(V, "V", dt, (B, Lc, d.n_kv_heads, d.seq_len, d.head_dim))
+    op = _dev(O, "O", dt, (B, Lc, d.n_q_heads, d.seq_len, d.head_dim))
+    sp = None if slot is None else _dev(slot, "slot", torch.int32, (B,))
+    rp = None if row_sel is None else _dev(row_sel, "row_sel", torch.int32, (B,))
+    fdt = torch.float16 if d.emb_dtype == AC_F16 else torch.float32
+    fp = None if feat is None else _dev(feat, "feat", fdt, (B, d.emb_dim))
+    _check(lib().attncache_insert(db.handle, fp, sp, rp, qp, kp, vp, op, B, layer_begin, Lc,
+                                  float(scale), _stream(stream)), "attncache_insert")
 
 
 def attention_exact(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, O: torch.Tensor, *,

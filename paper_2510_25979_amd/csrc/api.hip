@@ -325,4 +325,38 @@ int32_t attention_exact(const void* Q, const void* K, const void* V, void* O,
   return e == hipSuccess ? AC_OK : hip_fail(e);
 }
 
+int32_t attncache_insert(attncache_db* db, const void* feat, const int32_t* slot,
+                         const int32_t* row_sel, const void* Q, const void* K, const void* V,
+                         void* O, int32_t B, int32_t layer_begin, int32_t layer_count, float scale,
+                         void* stream) {
+  if (!db) return AC_ERR_NULL;
+  const attncache_db_desc& d = db->d;
+  if (B < 0 || layer_begin < 0 || layer_count < 0 || layer_begin + layer_count > d.n_layers)
+    return AC_ERR_SHAPE;
+  if (d.map_dtype != AC_BF16) return AC_ERR_DTYPE;
+  if (d.maps_on_host) return AC_ERR_MEMSPACE;
+  // a slot names a map entry AND a feature row: the two stores must share one index
+  if (feat && (db->map_of || d.n_emb != d.n_entries)) return AC_ERR_SHAPE;
+  const size_t esz = d.emb_dtype == AC_F16 ? 2 : 4;
+  if (feat && (d.emb_dim * esz) % 16 != 0) return AC_ERR_SHAPE;
+  if (!(scale >= 0.f)) return AC_ERR_SHAPE;
+  if (B == 0 || layer_count == 0) return AC_OK;
+  if (!Q || !K || !V || !O) return AC_ERR_NULL;
+  if (feat && !slot) return AC_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(feat))
+    return AC_ERR_ALIGN;
+  ac::InsertLaunch p;
+  p.Q = Q; p.K = K; p.V = V; p.O = O;
+  p.maps = const_cast<void*>(db->maps);   // the one entry point that writes the borrowed stores
+  p.feat = feat; p.emb = const_cast<void*>(db->emb);
+  p.slot = slot; p.row_sel = row_sel;
+  p.B = B; p.M = d.n_entries; p.L = d.n_layers; p.layer_begin = layer_begin; p.Lc = layer_count;
+  p.Hq = d.n_q_heads; p.Hkv = d.n_kv_heads; p.S = d.seq_len; p.D = d.head_dim;
+  p.causal = d.causal != 0; p.packed = d.map_layout == AC_LAYOUT_PACKED;
+  p.emb_row_bytes = (int32_t)(d.emb_dim * esz);
+  p.scale = scale;
+  hipError_t e = ac::launch_insert(p, reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AC_OK : hip_fail(e);
+}
+
 }  // extern "C"

@@ -1,0 +1,274 @@
+// Database building on the device (Fig. 3, steps 2 and 3): the recompute branch of Algorithm 2
+// for inputs that are to be remembered.  For every selected item the kernel computes
+// O = softmax(scale * Q K^T) V like attention_exact, and ALSO writes the normalised map
+// A = softmax(scale * Q K^T) of every (layer, head), rounded once to bf16, into the item's slot
+// of the map store, in the store's layout; a second small kernel copies the item's feature
+// vector into the same slot of the feature store.  A later search that hits the slot makes
+// attncache_apply reproduce this O from the stored map.
+//
+// The map has to be normalised before it is written, so the row statistics must be known before
+// the first weight leaves: two passes over the keys.  Pass 1 forms the scores and keeps only the
+// row maximum m and the row sum l of 2^(score - m); pass 2 forms the scores again, turns them
+// into a = 2^(score - m) / l, rounds to bf16, stores them and multiplies the ROUNDED weights
+// with V (so O is exactly what the stored map yields, up to summation order).  Same transposed
+// products and register hand-over as the exact kernel: S^T = K Q^T (a lane holds 16 keys of one
+// query row), O^T = V^T A^T with A taken from the first product's result registers.
+// For S <= 128 K and V are staged in LDS once and both passes read them there; longer sequences
+// re-stage 128-key chunks in the second pass (L2 hits).
+//
+// Packed layout (see pack_maps_kernel): the result registers of one 32 x 32 score block map onto
+// packed 16 x 32 blocks directly -- register group q (4 registers) of lane (row i, half kh) is
+// elements 4 kh .. 4 kh + 3 of piece (16 q + i % 16), i.e. one 8-byte store per group, and the 32
+// lanes of a 16-row half fill a contiguous 256-byte run.
+#include "common.hpp"
+#include "launch.hpp"
+
+namespace ac {
+
+constexpr int kKPadI = 8;   // elements of padding per staged K row
+
+struct InsertArgs {
+  const void *Q, *K, *V;
+  void *O, *maps;
+  const int32_t *slot, *row_sel;
+  int32_t B, M, L, layer_begin, Lc, Hq, Hkv, S;
+  int32_t n_rblk, n_tiles;
+  float scale_log2e;
+};
+
+template <int D, bool CAUSAL, bool PACKED>
+__global__ __launch_bounds__(kThreads, 2) void insert_bf16_kernel(const InsertArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int KS = D + kKPadI;
+  bf16_t* ks_lds = reinterpret_cast<bf16_t*>(smem);   // [128][KS]; the output tile is staged here
+  bf16_t* vt = ks_lds + kChunk * KS;                  // [D][kVtStride]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int il = lane & 31, kh = lane >> 5;
+  const int S = a.S, g = a.Hq / a.Hkv;
+
+  // all row blocks of one (item, layer, head) get ids that are equal mod 8 (same XCD / L2)
+  const int bid = blockIdx.x;
+  const int tile = (bid >> 3) / a.n_rblk * 8 + (bid & 7);
+  const int R = a.n_rblk - 1 - (bid >> 3) % a.n_rblk;
+  if (tile >= a.n_tiles) return;
+  const int h = tile % a.Hq;
+  const int l = (tile / a.Hq) % a.Lc;
+  const int b = tile / (a.Hq * a.Lc);
+  if (a.row_sel && a.row_sel[b] >= 0) return;
+  const int entry = a.slot ? a.slot[b] : -1;
+  const bool keep = entry >= 0 && entry < a.M;   // anything else: compute O only
+
+  const size_t kv = (((size_t)b * a.Lc + l) * a.Hkv + h / g) * (size_t)S * D;
+  const bf16_t* Kt = reinterpret_cast<const bf16_t*>(a.K) + kv;
+  const bf16_t* Vt_src = reinterpret_cast<const bf16_t*>(a.V) + kv;
+  const size_t qo = (((size_t)b * a.Lc + l) * a.Hq + h) * (size_t)S * D;
+  const int n_chunk = CAUSAL ? R + 1 : (S + kChunk - 1) / kChunk;
+  const int r0 = R * kChunk + 32 * wave;
+  const bool active = r0 < S;
+  const int n32 = S >> 5;
+  const size_t tile_elems = PACKED ? (size_t)packed_blocks(S, CAUSAL) * 512 : (size_t)S * S;
+  bf16_t* At = reinterpret_cast<bf16_t*>(a.maps) +
+               (((size_t)(keep ? entry : 0) * a.L + (a.layer_begin + l)) * a.Hq + h) * tile_elems;
+
+  u32x4 q[D / 16];
+  if (active) {
+    const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.Q) + qo + (size_t)(r0 + il) * D + 8 * kh;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) q[ks] = *reinterpret_cast<const u32x4*>(qrow + 16 * ks);
+  }
+
+  auto stage_k = [&](int c) {
+    const int j0 = c * kChunk, nj = min(kChunk, S - j0);
+    constexpr int DQ = D / 8;
+    const u32x4* src = reinterpret_cast<const u32x4*>(Kt + (size_t)j0 * D);
+    for (int p = tid; p < nj * DQ; p += kThreads) {
+      const int j = p / DQ, dq = p % DQ;
+      *reinterpret_cast<u32x4*>(ks_lds + j * KS + 8 * dq) = src[p];
+    }
+  };
+  auto stage_v = [&](int c) {
+    const int j0 = c * kChunk;
+    stage_v_transposed<D>(Vt_src + (size_t)j0 * D, min(kChunk, S - j0), vt, tid);
+  };
+  // 32-key blocks of chunk c this wave's rows see
+  auto blocks = [&](int c) {
+    if (!active) return 0;
+    const int j0 = c * kChunk;
+    int nblk = min(kChunk, S - j0) >> 5;
+    if (CAUSAL) nblk = min(nblk, (r0 - j0) / 32 + 1);
+    return max(nblk, 0);
+  };
+  // scores^T of key block jb of the staged chunk (keys beyond the diagonal hidden)
+  auto scores = [&](int c, int jb) {
+    f32x16 s;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[v] = 0.f;
+    const bf16_t* krow = ks_lds + (32 * jb + il) * KS + 8 * kh;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks)
+      s = mfma_bf16(*reinterpret_cast<const bf16x8*>(krow + 16 * ks), __builtin_bit_cast(bf16x8, q[ks]), s);
+    if (CAUSAL && c * kChunk + 32 * jb == r0) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (mfma_row(v, kh) > il) s[v] = -INFINITY;
+    }
+    return s;
+  };
+
+  // ---- pass 1: row maximum m (log2 domain, scale folded in) and row sum l of 2^(score - m)
+  float m_run = -INFINITY, l_run = 0.f;
+  for (int c = 0; c < n_chunk; ++c) {
+    if (c > 0) __syncthreads();
+    stage_k(c);
+    if (n_chunk == 1) stage_v(0);   // short sequences: V is staged once, next to K
+    __syncthreads();
+    const int nblk = blocks(c);
+    for (int jb = 0; jb < nblk; ++jb) {
+      const f32x16 s = scores(c, jb);
+      float mx = s[0];
+#pragma unroll
+      for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run, mx * a.scale_log2e);
+      float psum = 0.f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) psum += __builtin_amdgcn_exp2f(fmaf(s[v], a.scale_log2e, -m_new));
+      l_run = l_run * __builtin_amdgcn_exp2f(m_run - m_new) + psum;
+      m_run = m_new;
+    }
+  }
+  const float inv_l = 1.0f / (l_run + __shfl_xor(l_run, 32));
+
+  // ---- pass 2: normalised weights, rounded, stored, multiplied with V
+  f32x16 acc[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+
+  // where register group q4 (scores 4 q4 .. 4 q4 + 3 of this lane) of key block kb goes
+  const int r16 = (r0 >> 4) + (il >> 4);
+  auto map_piece = [&](int kb, int q4) -> u32x2* {
+    if (PACKED) {
+      const int blk = (CAUSAL ? packed_prefix(r16) : r16 * n32) + kb;
+      return reinterpret_cast<u32x2*>(At + (size_t)blk * 512 + (16 * q4 + (il & 15)) * 8 + 4 * kh);
+    }
+    return reinterpret_cast<u32x2*>(At + (size_t)(r0 + il) * S + 32 * kb + 8 * q4 + 4 * kh);
+  };
+
+  for (int c = 0; c < n_chunk; ++c) {
+    if (n_chunk > 1) {
+      __syncthreads();
+      stage_k(c);
+      stage_v(c);
+      __syncthreads();
+    }
+    const int nblk = blocks(c);
+    for (int jb = 0; jb < nblk; ++jb) {
+      f32x16 s = scores(c, jb);
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        s[v] = __builtin_amdgcn_exp2f(fmaf(s[v], a.scale_log2e, -m_run)) * inv_l;
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        u32x4 pw;
+        pw.x = pack_bf16(s[8 * s2 + 0], s[8 * s2 + 1]);
+        pw.y = pack_bf16(s[8 * s2 + 2], s[8 * s2 + 3]);
+        pw.z = pack_bf16(s[8 * s2 + 4], s[8 * s2 + 5]);
+        pw.w = pack_bf16(s[8 * s2 + 6], s[8 * s2 + 7]);
+        if (keep) {
+          const int kb = 4 * c + jb;
+          *map_piece(kb, 2 * s2) = u32x2{pw.x, pw.y};
+          *map_piece(kb, 2 * s2 + 1) = u32x2{pw.z, pw.w};
+        }
+        const bf16x8 pop = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) {
+          const bf16_t* vrow = vt + (32 * db + il) * kVtStride + 32 * jb + 16 * s2 + 4 * kh;
+          u32x2 lo = *reinterpret_cast<const u32x2*>(vrow);
+          u32x2 hi = *reinterpret_cast<const u32x2*>(vrow + 8);
+          u32x4 w = {lo.x, lo.y, hi.x, hi.y};
+          acc[db] = mfma_bf16(__builtin_bit_cast(bf16x8, w), pop, acc[db]);
+        }
+      }
+    }
+  }
+  // A dense causal map carries its zeros: the 32-column blocks right of the diagonal block
+  // (the packed layout does not store them)
+  if (CAUSAL && !PACKED && keep && active) {
+    for (int kb = (r0 >> 5) + 1; kb < n32; ++kb)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) *map_piece(kb, q4) = u32x2{0u, 0u};
+  }
+
+  __syncthreads();   // K is dead: the output tiles are staged on top of it
+  if (active) {
+    bf16_t* Oh = reinterpret_cast<bf16_t*>(a.O) + qo + (size_t)r0 * D;
+    store_tile_bf16<D>(acc, 1.0f, ks_lds + wave * (32 * (D + 4)), Oh, lane);
+  }
+}
+
+// feature vector of item b into row slot[b] of the feature store (16-byte pieces)
+__global__ __launch_bounds__(kThreads) void insert_features_kernel(const u32x4* __restrict__ feat,
+                                                                   u32x4* __restrict__ emb,
+                                                                   const int32_t* __restrict__ slot,
+                                                                   const int32_t* __restrict__ row_sel,
+                                                                   int32_t M, int32_t pieces) {
+  const int b = blockIdx.x;
+  if (row_sel && row_sel[b] >= 0) return;
+  const int entry = slot[b];
+  if (entry < 0 || entry >= M) return;
+  for (int p = threadIdx.x; p < pieces; p += kThreads)
+    emb[(size_t)entry * pieces + p] = feat[(size_t)b * pieces + p];
+}
+
+static size_t insert_lds_bytes(int D) {
+  return (size_t)(kChunk * (D + kKPadI) + D * kVtStride) * sizeof(bf16_t);
+}
+
+template <int D, bool CAUSAL, bool PACKED>
+static hipError_t launch_insert_t(const InsertArgs& a, dim3 grid, hipStream_t stream) {
+  const size_t lds = insert_lds_bytes(D);
+  hipError_t e = ensure_lds<&insert_bf16_kernel<D, CAUSAL, PACKED>>(lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((insert_bf16_kernel<D, CAUSAL, PACKED>), grid, dim3(kThreads), lds, stream, a);
+  return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_insert_d(const InsertArgs& a, dim3 grid, bool causal, bool packed,
+                                  hipStream_t stream) {
+  if (causal) return packed ? launch_insert_t<D, true, true>(a, grid, stream)
+                            : launch_insert_t<D, true, false>(a, grid, stream);
+  return packed ? launch_insert_t<D, false, true>(a, grid, stream)
+                : launch_insert_t<D, false, false>(a, grid, stream);
+}
+
+// Host launcher.  Shapes were validated by the caller (api.hip).
+hipError_t launch_insert(const InsertLaunch& p, hipStream_t stream) {
+  if (p.B == 0 || p.Lc == 0) return hipSuccess;
+  if (p.feat) {
+    hipLaunchKernelGGL(insert_features_kernel, dim3((unsigned)p.B), dim3(kThreads), 0, stream,
+                       reinterpret_cast<const u32x4*>(p.feat), reinterpret_cast<u32x4*>(p.emb),
+                       p.slot, p.row_sel, p.M, p.emb_row_bytes / 16);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  InsertArgs a;
+  a.Q = p.Q; a.K = p.K; a.V = p.V; a.O = p.O; a.maps = p.maps;
+  a.slot = p.slot; a.row_sel = p.row_sel;
+  a.B = p.B; a.M = p.M; a.L = p.L; a.layer_begin = p.layer_begin; a.Lc = p.Lc;
+  a.Hq = p.Hq; a.Hkv = p.Hkv; a.S = p.S;
+  a.n_rblk = (p.S + kChunk - 1) / kChunk;
+  a.n_tiles = p.B * p.Lc * p.Hq;
+  const float scale = p.scale == 0.f ? 1.0f / sqrtf((float)p.D) : p.scale;
+  a.scale_log2e = scale * 1.44269504088896340736f;
+  const int tiles8 = (a.n_tiles + 7) / 8 * 8;
+  const dim3 grid((unsigned)((size_t)tiles8 * a.n_rblk));
+  return p.D == 64 ? launch_insert_d<64>(a, grid, p.causal, p.packed, stream)
+                   : launch_insert_d<128>(a, grid, p.causal, p.packed, stream);
+}
+
+}  // namespace ac

@@ -51,6 +51,20 @@ struct ExactLaunch {
 };
 hipError_t launch_exact(const ExactLaunch& p, hipStream_t stream);
 
+struct InsertLaunch {
+  const void *Q, *K, *V;   // device [B][Lc][Hq|Hkv][S][D] bf16
+  void* O;                 // device [B][Lc][Hq][S][D] bf16
+  void* maps;              // device: the whole map store (bf16, dense or packed)
+  const void* feat;        // device [B][E] or nullptr (maps only)
+  void* emb;               // device: the whole feature store
+  const int32_t* slot;     // device [B] or nullptr (compute O only)
+  const int32_t* row_sel;  // device [B] or nullptr
+  int32_t B, M, L, layer_begin, Lc, Hq, Hkv, S, D, causal, packed;
+  int32_t emb_row_bytes;
+  float scale;
+};
+hipError_t launch_insert(const InsertLaunch& p, hipStream_t stream);
+
 struct SearchLaunch {
   const void* emb;        // device [N][E]
   const void* q;          // device [B][E]

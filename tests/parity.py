@@ -70,3 +70,36 @@ def max_abs_err(gpu_out: torch.Tensor, oracle_out: np.ndarray) -> float:
     assert g.shape == oracle_out.shape
     assert np.isfinite(g).all()
     return float(np.abs(g - oracle_out).max())
+
+
+def unpack_map(packed: np.ndarray, S: int, causal: bool) -> np.ndarray:
+    """Dense [S,S] view of one map stored in the block-packed layout the header documents
+    (written here from that description, independently of the library): rows in blocks of 16,
+    columns in blocks of 32; row block r keeps its first ceil((r+1)/2) column blocks (causal) or
+    all of them; blocks row-block-major; inside a block element (i, 8q+e) sits at (16q+i)*8+e.
+    Blocks that are not stored read as zeros."""
+    out = np.zeros((S, S), packed.dtype)
+    n32 = S // 32
+    pos = 0
+    for r in range(S // 16):
+        nc = (r + 2) // 2 if causal else n32
+        for cb in range(nc):
+            blk = packed[pos:pos + 512].reshape(4, 16, 8)          # [q][i][e]
+            out[16 * r:16 * r + 16, 32 * cb:32 * cb + 32] = blk.transpose(1, 0, 2).reshape(16, 32)
+            pos += 512
+    assert pos == packed.size
+    return out
+
+
+def check_stored_map(gpu_map: np.ndarray, oracle_map_rounded: np.ndarray):
+    """A stored bf16 map against the oracle's map rounded to bf16.  The GPU forms the weights in
+    fp32 (relative error ~1e-6) before the one rounding, the oracle in fp64: the two can land on
+    neighbouring bf16 values when the exact weight lies next to a rounding boundary, never
+    further apart.  Bar: every element within one bf16 ulp (2^-7 relative), at most 2 % of the
+    elements different at all, zeros exactly zero."""
+    g = gpu_map.astype(np.float64)
+    r = oracle_map_rounded.astype(np.float64)
+    assert g.shape == r.shape and np.isfinite(g).all()
+    assert (g[r == 0.0] == 0.0).all()
+    assert (np.abs(g - r) <= 2.0 ** -7 * np.maximum(np.abs(r), 1e-38)).all()
+    assert (g != r).mean() <= 0.02

@@ -350,6 +350,119 @@ def test_whole_step_replayed_from_a_hip_graph_matches_eager(ac, oracle_mod):
     db.close()
 
 
+@pytest.mark.parametrize("causal", [True, False])
+def test_pack_maps_writes_the_documented_layout(ac, causal):
+    # the library's packer against the test suite's own reading of the documented layout
+    M, L, Hq, S = 2, 1, 3, 160
+    maps = _maps(M, L, Hq, S, torch.bfloat16, causal, 880)
+    packed = torch.empty(M, L, Hq, ac.packed_tile_elems(S, causal), dtype=torch.bfloat16, device="cuda")
+    ac.attncache_pack_maps(maps.cuda(), packed, causal=causal)
+    torch.cuda.synchronize()
+    ph, dh = parity.to_np(packed), parity.to_np(maps)
+    for m in range(M):
+        for h in range(Hq):
+            assert np.array_equal(parity.unpack_map(ph[m, 0, h], S, causal), dh[m, 0, h])
+
+
+INSERT_CASES = [
+    # B, L, Hq, Hkv, S, D, causal
+    (3, 2, 4, 2, 128, 64, True),
+    (2, 1, 2, 2, 96, 128, True),
+    (2, 1, 2, 1, 288, 64, True),      # three key chunks, ragged last row block
+    (2, 1, 2, 2, 160, 128, False),    # dense maps, ragged last chunk
+]
+
+
+@pytest.mark.parametrize("layout", ["dense", "packed"])
+@pytest.mark.parametrize("case", INSERT_CASES, ids=lambda c: "B%d-L%d-H%d/%d-S%d-D%d-%s" % (
+    c[0], c[1], c[2], c[3], c[4], c[5], "causal" if c[6] else "dense"))
+def test_insert_stores_the_oracles_map_and_output(ac, oracle_mod, case, layout):
+    B, L, Hq, Hkv, S, D, causal = case
+    M, E = 6, 32
+    g = _gen(900 + S + D)
+    Q = torch.randn(B, L, Hq, S, D, generator=g).to(torch.bfloat16)
+    K = torch.randn(B, L, Hkv, S, D, generator=g).to(torch.bfloat16)
+    V = torch.randn(B, L, Hkv, S, D, generator=g).to(torch.bfloat16)
+    feat = torch.randn(B, E, generator=g).half()
+    tile = ac.packed_tile_elems(S, causal) if layout == "packed" else S * S
+    sentinel = 0.5
+    maps = torch.full((M, L, Hq, tile), sentinel, dtype=torch.bfloat16, device="cuda")
+    emb = torch.zeros(M, E, dtype=torch.float16, device="cuda")
+    db = ac.attncache_build_db(emb, maps if layout == "packed" else maps.view(M, L, Hq, S, S),
+                               n_kv_heads=Hkv, head_dim=D, causal=causal, seq_len=S)
+    slot = torch.tensor(([4, -1, 1] if B == 3 else [3, 0]), dtype=torch.int32)
+    O = torch.full((B, L, Hq, S, D), 7.0, dtype=torch.bfloat16, device="cuda")
+    ac.attncache_insert(db, Q.cuda(), K.cuda(), V.cuda(), O, slot=slot.cuda(), feat=feat.cuda())
+    torch.cuda.synchronize()
+
+    maps_h = parity.to_np(maps)
+    for l in range(L):
+        ref_O, P = oracle_mod.attention_exact(parity.to_np(Q[:, l]), parity.to_np(K[:, l]),
+                                              parity.to_np(V[:, l]), causal=causal, return_map=True)
+        assert parity.max_abs_err(O[:, l].contiguous(), ref_O) <= 2e-2
+        P_r = oracle_mod.round_maps(P, oracle_mod.ROUND_BF16)
+        for b in range(B):
+            if slot[b] < 0:
+                continue
+            for h in range(Hq):
+                stored = maps_h[slot[b], l, h]
+                got = parity.unpack_map(stored, S, causal) if layout == "packed" else stored.reshape(S, S)
+                parity.check_stored_map(got, P_r[b, h])
+    # nothing else was touched
+    used = {int(x) for x in slot if x >= 0}
+    for m in range(M):
+        if m not in used:
+            assert (maps_h[m] == sentinel).all()
+            assert (emb[m] == 0).all()
+    for b in range(B):
+        if slot[b] >= 0:
+            assert torch.equal(emb[int(slot[b])].cpu(), feat[b])
+    db.close()
+
+
+def test_insert_then_search_and_reuse_closes_the_loop(ac, oracle_mod):
+    # miss -> compute and remember -> the same input hits and the reuse branch returns the
+    # output the recompute branch produced (same rounded map, summed in another order)
+    B, M, L, Hq, Hkv, S, D, E = 4, 16, 2, 4, 2, 128, 64, 64
+    g = _gen(950)
+    Q = torch.randn(B, L, Hq, S, D, generator=g).to(torch.bfloat16).cuda()
+    K = torch.randn(B, L, Hkv, S, D, generator=g).to(torch.bfloat16).cuda()
+    V = torch.randn(B, L, Hkv, S, D, generator=g).to(torch.bfloat16).cuda()
+    feat = torch.nn.functional.normalize(torch.randn(B, E, generator=g), dim=-1).half().cuda()
+    maps = torch.zeros(M, L, Hq, ac.packed_tile_elems(S, True), dtype=torch.bfloat16, device="cuda")
+    emb = torch.zeros(M, E, dtype=torch.float16, device="cuda")
+    db = ac.attncache_build_db(emb, maps, n_kv_heads=Hkv, head_dim=D, causal=True, seq_len=S)
+    ws = torch.empty(ac.attncache_workspace_bytes(db.desc, B, 1), dtype=torch.uint8, device="cuda")
+    idx = torch.empty(B, 1, dtype=torch.int32, device="cuda")
+    score = torch.empty(B, 1, dtype=torch.float32, device="cuda")
+    hit = torch.empty(B, dtype=torch.int32, device="cuda")
+    ac.attncache_search(db, feat, 1, 0.9, idx, score, hit, ws)
+    assert (hit.cpu() == -1).all()                                   # empty database: all miss
+    slot = torch.tensor([9, 2, 15, 0], dtype=torch.int32).cuda()
+    O_first = torch.empty(B, L, Hq, S, D, dtype=torch.bfloat16, device="cuda")
+    # layer by layer, as a model forward would deliver the maps; the feature goes in once
+    for l in range(L):
+        O_l = torch.empty(B, 1, Hq, S, D, dtype=torch.bfloat16, device="cuda")
+        ac.attncache_insert(db, Q[:, l:l + 1].contiguous(), K[:, l:l + 1].contiguous(),
+                            V[:, l:l + 1].contiguous(), O_l, slot=slot,
+                            feat=feat if l == 0 else None, row_sel=hit, layer_begin=l)
+        O_first[:, l:l + 1] = O_l
+    ac.attncache_search(db, feat, 1, 0.9, idx, score, hit, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(hit, slot)
+    O_reuse = torch.empty_like(O_first)
+    ac.attncache_apply(db, hit, V, O_reuse)
+    torch.cuda.synchronize()
+    diff = (O_reuse.float() - O_first.float()).abs()
+    assert diff.max().item() <= 2e-2
+    assert (diff > 0).float().mean().item() <= 0.05                  # mostly bit-equal
+    ref = oracle_mod.attention_exact(parity.to_np(Q.view(B, L * Hq, S, D)),
+                                     parity.to_np(K.view(B, L * Hkv, S, D)),
+                                     parity.to_np(V.view(B, L * Hkv, S, D)))
+    assert parity.max_abs_err(O_reuse.view(B, L * Hq, S, D), ref) <= 2e-2
+    db.close()
+
+
 def test_error_codes(ac):
     emb = torch.zeros(64, 128, dtype=torch.float16, device="cuda")
     maps = torch.zeros(64, 1, 2, 32, 32, dtype=torch.bfloat16, device="cuda")
@@ -389,5 +502,22 @@ def test_error_codes(ac):
         x = torch.zeros(1, 1, 40, 64, dtype=torch.bfloat16, device="cuda")
         ac.attention_exact(x, x, x, x.clone())
     assert e.value.status == -2
+    Qi = torch.zeros(4, 1, 2, 32, 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(ac.AttnCacheError) as e:       # insertion beyond the database's layers
+        ac.attncache_insert(db, Qi, V, V, O, slot=hit, layer_begin=1)
+    assert e.value.status == -2
+    many = torch.zeros(128, 128, dtype=torch.float16, device="cuda")   # two feature rows per entry
+    db2 = ac.attncache_build_db(many, maps, n_kv_heads=2, head_dim=64,
+                                map_of=(torch.arange(128, device="cuda") % 64).int())
+    with pytest.raises(ac.AttnCacheError) as e:       # a slot must name one feature row
+        ac.attncache_insert(db2, Qi, V, V, O, slot=hit, feat=q)
+    assert e.value.status == -2
+    db2.close()
+    f32db = ac.attncache_build_db(torch.zeros(8, 16, device="cuda"),
+                                  torch.zeros(8, 1, 2, 32, 32, device="cuda"), n_kv_heads=2, head_dim=64)
+    with pytest.raises(ac.AttnCacheError) as e:       # maps are written as bf16 only
+        ac.attncache_insert(f32db, Qi, V, V, O, slot=hit)
+    assert e.value.status == -3
+    f32db.close()
     ac.attncache_search(db, q, 1, 0.5, idx, score, hit, ws)   # the handle still works
     torch.cuda.synchronize()
