@@ -147,9 +147,15 @@ int32_t attncache_pack_maps(const attncache_db_desc *desc, const void *dense,
  *             above the diagonal is 0.  One entry is one contiguous block (all
  *             layers of one item lie together, as the paper's layer-adjacent
  *             layout).
- *   staging   DEVICE ring buffer of staging_bytes, used only when
- *             maps_on_host; must hold at least two entries.  NULL / 0
- *             otherwise.
+ *   staging   DEVICE buffer of staging_bytes, used only when maps_on_host;
+ *             must hold at least two entries.  NULL / 0 otherwise.  It is
+ *             managed as a cache of whole entries (floor(staging_bytes /
+ *             entry bytes) slots, least recently used slot replaced first):
+ *             an entry that an earlier attncache_apply left there is reused
+ *             without a new copy, so spare HBM given here absorbs the popular
+ *             entries of a skewed request stream (Sec. 3.1, locality of the
+ *             stored maps).  The host maps must not change while the handle
+ *             lives, or attncache_cache_reset() must be called.
  *   side_stream  hipStream_t on which host-to-device map copies are issued;
  *             used only when maps_on_host (must differ from the stream
  *             later passed to attncache_apply).
@@ -204,9 +210,12 @@ int32_t attncache_search(const attncache_db *db, const void *q, int32_t B,
  *             Rows of misses (hit[b] == -1) are not written.
  *
  * Device-resident maps: hit values outside [-1, M) are treated as misses by
- * the kernel (never dereferenced).  Host-resident maps: copies run on the
- * side stream into the staging ring and are overlapped with the products on
- * `stream`; on return all work is enqueued, nothing is waited for.
+ * the kernel (never dereferenced).  Host-resident maps: entries not yet in
+ * the staging cache are copied on the side stream (one copy per distinct
+ * entry, shared by all queries that hit it) and overlapped with the products
+ * on `stream`; on return all work is enqueued, nothing is waited for.  Calls
+ * on one handle must be issued in order (one stream, or ordered by the
+ * caller): a slot remembers only its latest reader.
  * fp32 accumulation; bf16 results are rounded once (nearest even).
  */
 int32_t attncache_apply(const attncache_db *db, const int32_t *hit,
@@ -277,6 +286,19 @@ int32_t attncache_insert(attncache_db *db, const void *feat,
                          const void *Q, const void *K, const void *V, void *O,
                          int32_t B, int32_t layer_begin, int32_t layer_count,
                          float scale, void *stream);
+
+/*
+ * Counters of the entry cache of a host-resident database since build /
+ * reset: lookups = distinct entries requested, summed over attncache_apply
+ * calls; copies = host-to-device entry copies issued.  HOST pointers.
+ */
+int32_t attncache_cache_stats(const attncache_db *db, uint64_t *lookups,
+                              uint64_t *copies);
+
+/* Forget every cached entry (after the host maps were modified) and zero the
+ * counters.  The caller must have synchronised the streams the handle was
+ * used on. */
+int32_t attncache_cache_reset(attncache_db *db);
 
 /* Short constant description of a status code. */
 const char *attncache_status_string(int32_t status);

@@ -27,7 +27,7 @@ _DTYPE_CODE = {torch.float32: AC_F32, torch.float16: AC_F16, torch.bfloat16: AC_
 SYMBOLS = ["attncache_workspace_bytes", "attncache_map_entry_bytes", "attncache_pack_maps",
            "attncache_build_db", "attncache_destroy_db",
            "attncache_search", "attncache_apply", "attention_exact", "attncache_insert",
-           "attncache_status_string",
+           "attncache_cache_stats", "attncache_cache_reset", "attncache_status_string",
            "attncache_last_hip_error", "attncache_version"]
 
 
@@ -81,6 +81,10 @@ def lib():
         L.attention_exact.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, f32, vp]
         L.attncache_insert.restype = i32
         L.attncache_insert.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp]
+        L.attncache_cache_stats.restype = i32
+        L.attncache_cache_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
+        L.attncache_cache_reset.restype = i32
+        L.attncache_cache_reset.argtypes = [vp]
         L.attncache_status_string.restype = ctypes.c_char_p
         L.attncache_status_string.argtypes = [i32]
         L.attncache_last_hip_error.restype = i32
@@ -250,6 +254,17 @@ def attncache_apply(db: Database, hit: torch.Tensor, V: torch.Tensor, O: torch.T
         hp = _dev(hit, "hit", torch.int32, (B,))
     _check(lib().attncache_apply(db.handle, hp, vp, op, B, layer_begin, Lc, _stream(stream)),
            "attncache_apply")
+
+
+def attncache_cache_stats(db: Database):
+    """(lookups, copies) of the entry cache of a host-resident database."""
+    a, b = ctypes.c_uint64(), ctypes.c_uint64()
+    _check(lib().attncache_cache_stats(db.handle, ctypes.byref(a), ctypes.byref(b)), "attncache_cache_stats")
+    return a.value, b.value
+
+
+def attncache_cache_reset(db: Database) -> None:
+    _check(lib().attncache_cache_reset(db.handle), "attncache_cache_reset")
 
 
 def attncache_insert(db: Database, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, O: torch.Tensor, *,

@@ -7,6 +7,8 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <list>
+#include <unordered_map>
 #include <vector>
 
 #include "../../include/attncache.h"
@@ -82,11 +84,16 @@ struct attncache_db {
   unsigned char* staging;
   size_t entry_bytes;
   int n_slots;
-  int next_slot;
   hipStream_t side;
   std::vector<hipEvent_t> copied;     // per slot: host-to-device copy finished
   std::vector<hipEvent_t> consumed;   // per slot: last product reading the slot finished
   std::vector<char> used;             // per slot: consumed[] has been recorded at least once
+  // slot cache: which entry (all layers) a slot holds, least recently used slot at the back
+  std::vector<int32_t> slot_entry;    // -1: nothing reusable
+  std::unordered_map<int32_t, int> where;
+  std::list<int> lru;
+  std::vector<std::list<int>::iterator> lru_it;
+  uint64_t lookups, copies;
 };
 
 extern "C" {
@@ -172,7 +179,7 @@ int32_t attncache_build_db(const attncache_db_desc* desc, const void* emb, const
   db->maps = maps;
   db->staging = nullptr;
   db->n_slots = 0;
-  db->next_slot = 0;
+  db->lookups = db->copies = 0;
   db->side = nullptr;
   db->entry_bytes = entry_bytes_of(desc);
   if (desc->maps_on_host) {
@@ -181,11 +188,14 @@ int32_t attncache_build_db(const attncache_db_desc* desc, const void* emb, const
     if (memspace(staging) != 0) { delete db; return AC_ERR_MEMSPACE; }
     if (staging_bytes / db->entry_bytes < 2) { delete db; return AC_ERR_WORKSPACE; }
     db->staging = reinterpret_cast<unsigned char*>(staging);
-    db->n_slots = (int)std::min<size_t>(staging_bytes / db->entry_bytes, 64);
+    db->n_slots = (int)std::min<size_t>(staging_bytes / db->entry_bytes, 1 << 16);
     db->side = reinterpret_cast<hipStream_t>(side_stream);
     db->copied.resize(db->n_slots);
     db->consumed.resize(db->n_slots);
     db->used.assign(db->n_slots, 0);
+    db->slot_entry.assign(db->n_slots, -1);
+    db->lru_it.resize(db->n_slots);
+    for (int i = 0; i < db->n_slots; ++i) db->lru_it[i] = db->lru.insert(db->lru.end(), i);
     for (int i = 0; i < db->n_slots; ++i) {
       hipError_t e = hipEventCreateWithFlags(&db->copied[i], hipEventDisableTiming);
       if (e == hipSuccess) e = hipEventCreateWithFlags(&db->consumed[i], hipEventDisableTiming);
@@ -257,9 +267,10 @@ int32_t attncache_apply(const attncache_db* cdb, const int32_t* hit, const void*
     return e == hipSuccess ? AC_OK : hip_fail(e);
   }
 
-  // Pinned-host maps: one host-to-device copy per distinct entry on the side stream, the
-  // products of all queries sharing that entry on the caller's stream as soon as the copy
-  // has landed.  Slots of the staging ring are recycled once their products are done.
+  // Pinned-host maps: at most one host-to-device copy per distinct entry on the side stream
+  // (none when the entry is still in the ring from an earlier batch), the products of all
+  // queries sharing that entry on the caller's stream as soon as the copy has landed.  A slot
+  // is overwritten only after the products that read it are done.
   for (int32_t b = 0; b < B; ++b)
     if (hit[b] < -1 || hit[b] >= d.n_entries) return AC_ERR_INDEX;
   std::vector<std::pair<int32_t, int32_t>> order;   // (entry, query), grouped by entry
@@ -275,15 +286,34 @@ int32_t attncache_apply(const attncache_db* cdb, const int32_t* hit, const void*
     const int32_t entry = order[pos].first;
     size_t end = pos;
     while (end < order.size() && order[end].first == entry) ++end;
-    const int slot = db->next_slot;
-    db->next_slot = (db->next_slot + 1) % db->n_slots;
+    // Slot cache: an entry that a previous batch (or an earlier group of this one) left in the
+    // ring is used where it lies; otherwise the least recently used slot is overwritten.  Only
+    // whole entries (all layers) are remembered.
+    const bool whole = layer_begin == 0 && layer_count == d.n_layers;
+    ++db->lookups;
+    int slot = -1;
+    bool cached = false;
+    if (whole) {
+      auto it = db->where.find(entry);
+      if (it != db->where.end()) { slot = it->second; cached = true; }
+    }
+    if (slot < 0) {
+      slot = db->lru.back();
+      if (db->slot_entry[slot] >= 0) db->where.erase(db->slot_entry[slot]);
+      db->slot_entry[slot] = whole ? entry : -1;
+      if (whole) db->where[entry] = slot;
+    }
+    db->lru.splice(db->lru.begin(), db->lru, db->lru_it[slot]);   // most recently used
     unsigned char* dst = db->staging + (size_t)slot * db->entry_bytes;
-    const unsigned char* src = reinterpret_cast<const unsigned char*>(db->maps) +
-                               (size_t)entry * db->entry_bytes + (size_t)layer_begin * layer_bytes;
     hipError_t e = hipSuccess;
-    if (db->used[slot]) e = hipStreamWaitEvent(db->side, db->consumed[slot], 0);
-    if (e == hipSuccess) e = hipMemcpyAsync(dst, src, copy_bytes, hipMemcpyHostToDevice, db->side);
-    if (e == hipSuccess) e = hipEventRecord(db->copied[slot], db->side);
+    if (!cached) {
+      ++db->copies;
+      const unsigned char* src = reinterpret_cast<const unsigned char*>(db->maps) +
+                                 (size_t)entry * db->entry_bytes + (size_t)layer_begin * layer_bytes;
+      if (db->used[slot]) e = hipStreamWaitEvent(db->side, db->consumed[slot], 0);
+      if (e == hipSuccess) e = hipMemcpyAsync(dst, src, copy_bytes, hipMemcpyHostToDevice, db->side);
+      if (e == hipSuccess) e = hipEventRecord(db->copied[slot], db->side);
+    }
     if (e == hipSuccess) e = hipStreamWaitEvent(stream, db->copied[slot], 0);
     if (e != hipSuccess) return hip_fail(e);
     // the staged block holds layers [layer_begin, layer_begin + layer_count) only
@@ -299,6 +329,21 @@ int32_t attncache_apply(const attncache_db* cdb, const int32_t* hit, const void*
     db->used[slot] = 1;
     pos = end;
   }
+  return AC_OK;
+}
+
+int32_t attncache_cache_stats(const attncache_db* db, uint64_t* lookups, uint64_t* copies) {
+  if (!db || !lookups || !copies) return AC_ERR_NULL;
+  *lookups = db->lookups;
+  *copies = db->copies;
+  return AC_OK;
+}
+
+int32_t attncache_cache_reset(attncache_db* db) {
+  if (!db) return AC_ERR_NULL;
+  db->where.clear();
+  std::fill(db->slot_entry.begin(), db->slot_entry.end(), -1);
+  db->lookups = db->copies = 0;
   return AC_OK;
 }
 

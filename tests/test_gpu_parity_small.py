@@ -463,6 +463,51 @@ def test_insert_then_search_and_reuse_closes_the_loop(ac, oracle_mod):
     db.close()
 
 
+def test_host_resident_maps_are_cached_across_batches(ac, oracle_mod):
+    # maps in pinned host memory, a cache of 4 entries in device memory: popular entries are
+    # copied once and reused by later batches, eviction takes the least recently used slot,
+    # and every batch still equals the oracle
+    M, L, Hq, Hkv, S, D = 12, 2, 2, 1, 128, 64
+    maps = _maps(M, L, Hq, S, torch.bfloat16, True, 990)
+    host_maps = torch.empty(maps.shape, dtype=torch.bfloat16, pin_memory=True)
+    host_maps.copy_(maps)
+    entry_bytes = L * Hq * S * S * 2
+    staging = torch.empty(4 * entry_bytes, dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    db = ac.attncache_build_db(torch.zeros(M, 16, device="cuda"), host_maps, n_kv_heads=Hkv,
+                               head_dim=D, staging=staging, side_stream=side)
+    maps_np = parity.to_np(maps)
+    batches = [([3, 3, 7, 1], 3),          # 3 distinct entries: 3 copies
+               ([7, 1, 1, 9], 1),          # 7 and 1 are still there: 1 copy
+               ([-1, 9, 9, 3], 0),         # a miss, and two cached entries: no copy
+               ([0, 2, 4, 5], 4),          # four new entries replace everything
+               ([9, 5, 4, 11], 2)]         # 5 and 4 survive, 9 was evicted
+    lookups = copies = 0
+    for n, (hits, new_copies) in enumerate(batches):
+        B = len(hits)
+        V = torch.randn(B, L, Hkv, S, D, generator=_gen(1000 + n)).to(torch.bfloat16)
+        O = torch.full((B, L, Hq, S, D), 7.0, dtype=torch.bfloat16, device="cuda")
+        hit = torch.tensor(hits, dtype=torch.int32)
+        ac.attncache_apply(db, hit, V.cuda(), O)
+        torch.cuda.synchronize()
+        ref = oracle_mod.apply(maps_np, hit.numpy(), parity.to_np(V), out=np.full((B, L, Hq, S, D), 7.0))
+        assert parity.max_abs_err(O, ref) <= 2e-2, n
+        lookups += len({h for h in hits if h >= 0})
+        copies += new_copies
+        assert ac.attncache_cache_stats(db) == (lookups, copies), n
+    # a layer sub-range is staged without being remembered
+    V = torch.randn(1, 1, Hkv, S, D, generator=_gen(1100)).to(torch.bfloat16)
+    O = torch.empty(1, 1, Hq, S, D, dtype=torch.bfloat16, device="cuda")
+    ac.attncache_apply(db, torch.tensor([5], dtype=torch.int32), V.cuda(), O, layer_begin=1, layer_count=1)
+    torch.cuda.synchronize()
+    ref = oracle_mod.apply(maps_np[:, 1:2], np.array([5], np.int32), parity.to_np(V))
+    assert parity.max_abs_err(O, ref) <= 2e-2
+    assert ac.attncache_cache_stats(db) == (lookups + 1, copies + 1)
+    ac.attncache_cache_reset(db)
+    assert ac.attncache_cache_stats(db) == (0, 0)
+    db.close()
+
+
 def test_error_codes(ac):
     emb = torch.zeros(64, 128, dtype=torch.float16, device="cuda")
     maps = torch.zeros(64, 1, 2, 32, 32, dtype=torch.bfloat16, device="cuda")
