@@ -8,7 +8,9 @@ workload is the Llama-3.2-1B-shaped one (16 layers x 32 heads, head_dim 64,
 S = 128, bf16; 10,000-entry database resident in HBM; batch 64, all planted).
 
 Prints ONE JSON line.  `value` is tokens/s of the whole step with every input
-already resident in HBM.  Beside it: the reuse-only and exact-only rates and
+already resident in HBM; the K timed steps are replays of one captured HIP
+graph of the step (`--launch eager` issues the library calls one by one
+instead; that figure is reported beside it either way).  Beside it: the reuse-only and exact-only rates and
 their ratio, search QPS, the roofline record of the dominant kernel (map
 reuse, HBM-bound) and the CPU oracle timed on a bounded sample.
 """
@@ -28,7 +30,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # (scaled by a plain copy of known size; the runs are summarised under profiles/), as a
 # multiple of the algorithmic bytes of the same launch.
 MEASURED_TRAFFIC_RATIO = {("llama-3.2-1b-shaped", "packed"): 1.0001,
-                          ("llama-3.2-1b-shaped", "dense"): 1.075}
+                          ("llama-3.2-1b-shaped", "dense"): 1.075,
+                          ("long-sequence-layer", "packed"): 1.0064}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 
 

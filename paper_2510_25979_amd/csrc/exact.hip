@@ -603,9 +603,10 @@ static size_t exact_lds_bytes(int D, int heads_per_wg) {
 template <int D, bool CAUSAL>
 static hipError_t launch_exact_bf16(ExactArgs a, dim3 grid, hipStream_t stream) {
   a.n_blocks = (int32_t)grid.x;
-  // routed launch: 8 workgroups per compute unit walk the tiles (a multiple of 8 keeps the
+  // routed launch: 32 workgroups per compute unit walk the tiles (enough of them for the
+  // hardware to even out an uneven mix of hits and misses; a multiple of 8 keeps the
   // tile -> XCD assignment of the one-tile-per-workgroup launch)
-  if (a.row_sel && grid.x > 2048u) grid.x = 2048u;
+  if (a.row_sel && grid.x > 8192u) grid.x = 8192u;
   const size_t lds = exact_lds_bytes(D, a.heads_per_wg);
   hipError_t e = ensure_lds<&exact_bf16_kernel<D, CAUSAL>>(lds);
   if (e != hipSuccess) return e;
