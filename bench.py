@@ -69,6 +69,10 @@ def main():
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="how the K timed steps are issued: replays of one captured HIP graph of "
                          "the step (default), or one library call after the other")
+    ap.add_argument("--per-layer", action="store_true",
+                    help="also time the per-layer mode (every layer runs its own search, reuse and "
+                         "recompute launch; the whole chain is one HIP graph) and report it as "
+                         "`per_layer_mode`")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 1 GiB device copy (a kernel of known HBM traffic "
@@ -179,6 +183,47 @@ def main():
         assert torch.equal(O, O_eager), "graph replay and eager step disagree"
         del O_eager
 
+    # ------------- per-layer mode (Sec. 5.3, the finer-grained variant): L x (search, reuse, exact)
+    per_layer = None
+    if args.per_layer:
+        Ql = [Q[:, l].contiguous() for l in range(L)]
+        Kl = [K[:, l].contiguous() for l in range(L)]
+        Vl = [V[:, l:l + 1].contiguous() for l in range(L)]
+        Ol = [torch.zeros(B, 1, Hq, S, D, dtype=dt, device=dev) for _ in range(L)]
+        hit_l = torch.empty(L, B, dtype=torch.int32, device=dev)
+
+        def chain():
+            for l in range(L):
+                ac.attncache_search(db, q, w.k, w.theta, idx, score, hit_l[l], ws)
+                ac.attncache_apply(db, hit_l[l], Vl[l], Ol[l], layer_begin=l, layer_count=1)
+                ac.attention_exact(Ql[l], Kl[l], Vl[l].view(B, Hkv, S, D), Ol[l].view(B, Hq, S, D),
+                                   causal=w.causal, row_sel=hit_l[l])
+
+        chain()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph_l = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph_l, stream=side):
+                chain()
+        torch.cuda.synchronize()
+        times = {}
+        for name, fn in (("graph", graph_l.replay), ("eager", chain)):
+            for _ in range(max(1, args.warmup)):
+                fn()
+            torch.cuda.synchronize()
+            t_start = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            times[name] = (time.perf_counter() - t_start) * 1e3 / args.steps
+        assert torch.equal(torch.cat(Ol, 1), O), "per-layer chain and whole-model step disagree"
+        per_layer = {"ms_per_step": times["graph"], "ms_per_step_eager": times["eager"],
+                     "tokens_per_s": B * S / (times["graph"] * 1e-3), "layers": L,
+                     "launches_per_step": 4 * L if w.k == 1 else 5 * L}
+        del Ql, Kl, Vl, Ol
+
     # ----------------------------------------- the denominator: exact attention on every query
     for _ in range(max(1, args.warmup // 2)):
         ac.attention_exact(Qf, Kf, Vf, Oef, causal=w.causal)
@@ -246,6 +291,9 @@ def main():
         "paper_context": "paper reports 2x (2x Xeon Silver 4410Y) and 3x (A100-80GB) attention-block "
                          "speedup, fp32 Llama-3-3B, incl. removed Q/K projections and RoPE",
     }
+
+    if per_layer is not None:
+        result["per_layer_mode"] = per_layer
 
     # ------------------------------------------- CPU oracle on a bounded sample (reported only)
     if not args.no_cpu_baseline:

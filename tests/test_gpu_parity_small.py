@@ -364,6 +364,79 @@ def test_pack_maps_writes_the_documented_layout(ac, causal):
             assert np.array_equal(parity.unpack_map(ph[m, 0, h], S, causal), dh[m, 0, h])
 
 
+def test_per_layer_search_and_reuse_chain_from_one_graph(ac, oracle_mod):
+    # per-layer mode (every layer searches its own feature store and reuses or recomputes on
+    # its own): L handles over ONE map store, each with its own feature vectors, driven with
+    # layer_begin = l; the whole chain of L x (search, reuse, exact) launches is one HIP graph
+    B, M, L, Hq, Hkv, S, D, E = 6, 32, 3, 4, 2, 128, 64, 32
+    g = _gen(1200)
+    maps = _maps(M, L, Hq, S, torch.bfloat16, True, 1201)
+    packed = torch.empty(M, L, Hq, ac.packed_tile_elems(S, True), dtype=torch.bfloat16, device="cuda")
+    ac.attncache_pack_maps(maps.cuda(), packed, causal=True)
+    embs = [torch.nn.functional.normalize(torch.randn(M, E, generator=g), dim=-1).half() for _ in range(L)]
+    dbs = [ac.attncache_build_db(embs[l].cuda(), packed, n_kv_heads=Hkv, head_dim=D, causal=True, seq_len=S)
+           for l in range(L)]
+    dev = torch.device("cuda")
+    q = [torch.empty(B, E, dtype=torch.float16, device=dev) for _ in range(L)]
+    Q = torch.empty(L, B, 1, Hq, S, D, dtype=torch.bfloat16, device=dev)
+    K = torch.empty(L, B, 1, Hkv, S, D, dtype=torch.bfloat16, device=dev)
+    V = torch.empty(L, B, 1, Hkv, S, D, dtype=torch.bfloat16, device=dev)
+    O = torch.empty(L, B, 1, Hq, S, D, dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(ac.attncache_workspace_bytes(dbs[0].desc, B, 1), dtype=torch.uint8, device=dev)
+    idx = torch.empty(L, B, 1, dtype=torch.int32, device=dev)
+    score = torch.empty(L, B, 1, dtype=torch.float32, device=dev)
+    hit = torch.empty(L, B, dtype=torch.int32, device=dev)
+
+    def chain(out):
+        for l in range(L):
+            ac.attncache_search(dbs[l], q[l], 1, 0.8, idx[l], score[l], hit[l], ws)
+            ac.attncache_apply(dbs[l], hit[l], V[l], out[l], layer_begin=l, layer_count=1)
+            ac.attention_exact(Q[l].view(B, Hq, S, D), K[l].view(B, Hkv, S, D), V[l].view(B, Hkv, S, D),
+                               out[l].view(B, Hq, S, D), causal=True, row_sel=hit[l])
+
+    def new_inputs(seed):
+        gg = _gen(seed)
+        want = torch.full((L, B), -1, dtype=torch.int64)
+        for l in range(L):
+            rows = torch.randint(0, M, (B,), generator=gg)
+            qq = embs[l][rows].float() + 0.02 * torch.randn(B, E, generator=gg)
+            miss = torch.rand(B, generator=gg) < 0.4            # a different hit pattern per layer
+            qq[miss] = torch.randn(B, E, generator=gg)[miss]
+            q[l].copy_(torch.nn.functional.normalize(qq, dim=-1).half())
+            want[l] = torch.where(miss, torch.full_like(rows, -1), rows)
+        for t in (Q, K, V):
+            t.copy_(torch.randn(t.shape, generator=gg).to(torch.bfloat16))
+        return want
+
+    new_inputs(1)
+    chain(O)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            chain(O)
+    torch.cuda.synchronize()
+    maps_np = parity.to_np(maps)
+    for seed in (2, 3):
+        want = new_inputs(seed)
+        O.fill_(5.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(hit.cpu().long(), want)
+        for l in range(L):
+            h = hit[l].cpu().numpy()
+            ref = oracle_mod.attention_exact(parity.to_np(Q[l, :, 0]), parity.to_np(K[l, :, 0]),
+                                             parity.to_np(V[l, :, 0]), causal=True, row_sel=h,
+                                             out=np.full((B, Hq, S, D), 5.0))
+            ref = oracle_mod.apply(maps_np[:, l:l + 1], h, parity.to_np(V[l]),
+                                   out=ref.reshape(B, 1, Hq, S, D))
+            assert parity.max_abs_err(O[l], ref) <= 2e-2, (seed, l)
+    for db in dbs:
+        db.close()
+
+
 INSERT_CASES = [
     # B, L, Hq, Hkv, S, D, causal
     (3, 2, 4, 2, 128, 64, True),
