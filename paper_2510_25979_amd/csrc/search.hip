@@ -198,17 +198,37 @@ __global__ __launch_bounds__(kThreads, 2) void search_f16_big_kernel(const Searc
   const f16_t* emb = reinterpret_cast<const f16_t*>(a.emb);
 
   // copy chunk ch into buf: instruction k = wave + 4 i fills LDS slots [64 k, 64 k + 64) of the
-  // chunk (slot = row * EQ + position); rows past the end are clamped (masked when compared)
+  // chunk (slot = row * EQ + position).  The element offset of the global piece a lane fetches
+  // with instruction i, relative to the chunk's first row, is fixed for the whole kernel.
+  unsigned coff[NDMA];
+#pragma unroll
+  for (int i = 0; i < NDMA; ++i) {
+    const int slot = kWave * (wave + 4 * i) + lane;
+    const int row = slot / EQ, pos = slot % EQ;
+    coff[i] = (unsigned)(row * E + 8 * (pos ^ (row & 15)));
+  }
   auto copy_in = [&](f16_t* buf, int ch) {
+    const f16_t* src = emb + (size_t)(row_begin + ch * kBigRows) * E;
 #pragma unroll
     for (int i = 0; i < NDMA; ++i) {
-      const int k = wave + 4 * i;
-      const int slot = kWave * k + lane;
+      const f16_t* piece = src + coff[i];
+      __builtin_amdgcn_global_load_lds(piece, buf + kWave * (wave + 4 * i) * 8, 16, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // the same for a chunk that reaches beyond the database: rows past the end repeat the last
+  // row (they are masked when compared)
+  auto copy_in_clamped = [&](f16_t* buf, int ch) {
+#pragma unroll
+    for (int i = 0; i < NDMA; ++i) {
+      const int slot = kWave * (wave + 4 * i) + lane;
       const int row = slot / EQ, pos = slot % EQ;
       const int piece = pos ^ (row & 15);
       const int r = min(row_begin + ch * kBigRows + row, a.N - 1);
-      __builtin_amdgcn_global_load_lds(emb + (size_t)r * E + 8 * piece, buf + kWave * k * 8, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(emb + (size_t)r * E + 8 * piece,
+                                       buf + kWave * (wave + 4 * i) * 8, 16, 0, 0);
     }
+    __builtin_amdgcn_sched_barrier(0);
   };
 
   float best_s[QPW];
@@ -216,43 +236,69 @@ __global__ __launch_bounds__(kThreads, 2) void search_f16_big_kernel(const Searc
 #pragma unroll
   for (int j = 0; j < QPW; ++j) { best_s[j] = -INFINITY; best_i[j] = kIdxNone; }
 
-  auto compute = [&](const f16_t* buf, int ch) {
-    const int cbase = row_begin + ch * kBigRows;
-    const bool ragged = cbase + kBigRows > row_end;   // only the last chunk can be
+  // RAGGED is a literal at both call sites and the body is inlined: the copy used for complete
+  // chunks carries no per-row tests
+  // LDS element offset of this lane's operand piece of contraction step ks (row il of a 32-row
+  // block; piece 2 ks + kh at position (2 ks + kh) ^ (il & 15)).  The exchange only touches the
+  // low four bits of the piece index, so steps ks and ks + 8 lie exactly 16 pieces apart:
+  // eight offsets serve every width, the rest is an immediate.
+  int eoff[8];
 #pragma unroll
-    for (int rb = 0; rb < kBigRows / 32; ++rb) {
+  for (int ks = 0; ks < 8; ++ks) eoff[ks] = il * E + 8 * ((2 * ks + kh) ^ (il & 15));
+  auto operand = [&](const f16_t* buf, int rb, int ks) {
+    return *reinterpret_cast<const f16x8*>(buf + eoff[ks & 7] + 128 * (ks >> 3) + 32 * rb * E);
+  };
+
+  // RAGGED is a literal at both call sites and the body is inlined: the copy used for complete
+  // chunks carries no per-row tests.  The operand reads run two steps ahead of the products
+  // (three operand registers in rotation), the fences keep that order in the instruction stream.
+  auto compute = [&](const f16_t* buf, int ch, const bool RAGGED) __attribute__((always_inline)) {
+    const int cbase = row_begin + ch * kBigRows;
+    constexpr int NRB = kBigRows / 32;
+    f16x8 eop[3];
+    eop[0] = operand(buf, 0, 0);
+    eop[1] = operand(buf, 0, 1);
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
       f32x16 acc[QPW];
 #pragma unroll
       for (int j = 0; j < QPW; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
-      const f16_t* erow = buf + (32 * rb + il) * E;
 #pragma unroll
       for (int ks = 0; ks < KSMAX; ++ks) {
-        const f16x8 eop = *reinterpret_cast<const f16x8*>(erow + 8 * ((2 * ks + kh) ^ (il & 15)));
+        const int t = rb * KSMAX + ks;   // step within the chunk: the reads run on into the next block
+        if (ks + 2 < KSMAX) eop[(t + 2) % 3] = operand(buf, rb, ks + 2);
+        else if (rb + 1 < NRB) eop[(t + 2) % 3] = operand(buf, rb + 1, ks + 2 - KSMAX);
 #pragma unroll
-        for (int j = 0; j < QPW; ++j) acc[j] = mfma_f16(eop, qop[j][ks], acc[j]);
+        for (int j = 0; j < QPW; ++j) acc[j] = mfma_f16(eop[t % 3], qop[j][ks], acc[j]);
+        __builtin_amdgcn_sched_barrier(0);
       }
       // acc[j][v] = <emb[r], q>.  A new best becomes rare as the scan proceeds, so first only the
       // block maximum is compared; the position is looked up only when some lane improved.
       // Rows ascend with v, rb and ch, so strict comparisons keep the lowest row among equals.
-      const int rbase = cbase + 32 * rb + 4 * kh;
-      if (ragged) {
+      if (RAGGED) {
+        const int rbase = cbase + 32 * rb + 4 * kh;
 #pragma unroll
         for (int j = 0; j < QPW; ++j)
 #pragma unroll
           for (int v = 0; v < 16; ++v)
             if (rbase + 8 * (v >> 2) + (v & 3) >= row_end) acc[j][v] = -INFINITY;
       }
+      // The position is remembered as a code that is uniform over the wave, (32-row block of
+      // the group) * 16 + register: candidates then cost no vector registers; the row is
+      // decoded once at the end.
+      const int code = (ch * (kBigRows / 32) + rb) << 4;
 #pragma unroll
       for (int j = 0; j < QPW; ++j) {
-        float mx = acc[j][0];
+        float mx = fmaxf(fmaxf(acc[j][0], acc[j][1]), acc[j][2]);
 #pragma unroll
-        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, acc[j][v]);
+        for (int v = 3; v < 15; v += 2) mx = fmaxf(fmaxf(mx, acc[j][v]), acc[j][v + 1]);
+        mx = fmaxf(mx, acc[j][15]);
         if (__any(mx > best_s[j])) {
 #pragma unroll
           for (int v = 0; v < 16; ++v)
-            if (acc[j][v] > best_s[j]) { best_s[j] = acc[j][v]; best_i[j] = rbase + 8 * (v >> 2) + (v & 3); }
+            if (acc[j][v] > best_s[j]) { best_s[j] = acc[j][v]; best_i[j] = code + v; }
         }
       }
     }
@@ -263,21 +309,36 @@ __global__ __launch_bounds__(kThreads, 2) void search_f16_big_kernel(const Searc
     __syncthreads();
   };
 
-  copy_in(buf0, 0);
+  // Complete chunks run through the test-free copy of the loop body, two per trip so that the
+  // buffers alternate without pointer arithmetic; a last incomplete chunk (end of the group
+  // or of the database) goes through the clamped copy and the masked comparison.
+  const int n_full = (row_end - row_begin) / kBigRows;
+  if (n_full > 0) copy_in(buf0, 0); else copy_in_clamped(buf0, 0);
   publish();
-  for (int ch = 0; ch < n_chunk; ch += 2) {
-    if (ch + 1 < n_chunk) copy_in(buf1, ch + 1);
-    compute(buf0, ch);
+  int ch = 0;
+  for (; ch + 1 < n_full; ch += 2) {
+    copy_in(buf1, ch + 1);
+    compute(buf0, ch, false);
     publish();
+    if (ch + 2 < n_full) copy_in(buf0, ch + 2);
+    else if (ch + 2 < n_chunk) copy_in_clamped(buf0, ch + 2);
+    compute(buf1, ch + 1, false);
+    publish();
+  }
+  for (; ch < n_chunk; ++ch) {   // at most one complete and one incomplete chunk are left
+    f16_t* cur = (ch & 1) ? buf1 : buf0;
+    f16_t* nxt = (ch & 1) ? buf0 : buf1;
     if (ch + 1 < n_chunk) {
-      if (ch + 2 < n_chunk) copy_in(buf0, ch + 2);
-      compute(buf1, ch + 1);
-      publish();
+      if (ch + 1 < n_full) copy_in(nxt, ch + 1); else copy_in_clamped(nxt, ch + 1);
     }
+    compute(cur, ch, true);
+    publish();
   }
   // combine the two lane halves; every wave owns its queries, nothing else to merge
 #pragma unroll
   for (int j = 0; j < QPW; ++j) {
+    if (best_i[j] != kIdxNone)   // code -> database row
+      best_i[j] = row_begin + 32 * (best_i[j] >> 4) + mfma_row(best_i[j] & 15, kh);
     const float so = __shfl_xor(best_s[j], 32);
     const int io = __shfl_xor(best_i[j], 32);
     if (ranks_before(so, io, best_s[j], best_i[j])) { best_s[j] = so; best_i[j] = io; }
@@ -432,7 +493,7 @@ __global__ __launch_bounds__(kThreads) void finalize_topk_kernel(const SearchArg
 enum { kModeValu = 0, kModeMfma = 1, kModeMfmaBig = 2 };
 constexpr int kBigBatch = 64;   // above this many queries the query-stationary kernel is used
 
-static void search_plan(int32_t N, int32_t mode, int32_t* rows_per_wg, int32_t* G) {
+static void search_plan(int32_t N, int32_t mode, int32_t k, int32_t* rows_per_wg, int32_t* G) {
   int rpw;
   if (mode == kModeMfma) {
     // 128 rows per pass of a workgroup; more passes per workgroup for large databases so that
@@ -442,11 +503,13 @@ static void search_plan(int32_t N, int32_t mode, int32_t* rows_per_wg, int32_t* 
     if (c > 8) c = 8;
     rpw = 128 * (int)c;
   } else if (mode == kModeMfmaBig) {
-    // chunks of 64 rows; enough chunks per workgroup to amortise loading the queries into
-    // registers, while keeping ~2000 workgroups
-    long c = ((long)N + 64L * 2048 - 1) / (64L * 2048);
+    // chunks of 64 rows.  Loading the queries into registers and filling the copy pipeline
+    // costs a workgroup as much as five chunks (measured), so a workgroup takes as many chunks
+    // as leave about 512 workgroups: two per compute unit, all resident at once.  With k > 1
+    // the second phase re-scores k whole groups per query, which caps the group size.
+    long c = ((long)N + 64L * 512 - 1) / (64L * 512);
     if (c < 1) c = 1;
-    if (c > 16) c = 16;
+    if (c > (k > 1 ? 16 : 64)) c = k > 1 ? 16 : 64;
     rpw = kBigRows * (int)c;
   } else {
     rpw = kValuRowsPerWg;
@@ -470,7 +533,7 @@ size_t search_workspace_bytes(int32_t N, int32_t E, int32_t B, int32_t k, int32_
   size_t need = 0;
   for (int metric = 0; metric < 2; ++metric) {
     int32_t rpw, G;
-    search_plan(N, search_mode(is_f16, metric, E, B), &rpw, &G);
+    search_plan(N, search_mode(is_f16, metric, E, B), k, &rpw, &G);
     size_t bytes = ((size_t)B * G * 8 + 255) / 256 * 256;
     if (k > 1) bytes += (size_t)B * k * rpw * 4;
     if (bytes > need) need = bytes;
@@ -516,7 +579,7 @@ hipError_t launch_search(const SearchLaunch& p, hipStream_t stream) {
   a.idx = p.idx; a.score = p.score; a.hit = p.hit;
   const int mode = search_mode(p.is_f16, p.metric, p.E, p.B);
   const bool mfma = mode == kModeMfma;
-  search_plan(p.N, mode, &a.rows_per_wg, &a.G);
+  search_plan(p.N, mode, p.k, &a.rows_per_wg, &a.G);
   unsigned char* ws = reinterpret_cast<unsigned char*>(p.ws);
   size_t part_bytes = ((size_t)p.B * a.G * 8 + 255) / 256 * 256;
   a.part_s = reinterpret_cast<float*>(ws);
