@@ -505,9 +505,9 @@ static void search_plan(int32_t N, int32_t mode, int32_t k, int32_t* rows_per_wg
   } else if (mode == kModeMfmaBig) {
     // chunks of 64 rows.  Loading the queries into registers and filling the copy pipeline
     // costs a workgroup as much as five chunks (measured), so a workgroup takes as many chunks
-    // as leave about 512 workgroups: two per compute unit, all resident at once.  With k > 1
+    // as leave about 480 workgroups: just under two per compute unit, all resident at once.  With k > 1
     // the second phase re-scores k whole groups per query, which caps the group size.
-    long c = ((long)N + 64L * 512 - 1) / (64L * 512);
+    long c = ((long)N + 64L * 480 - 1) / (64L * 480);
     if (c < 1) c = 1;
     if (c > (k > 1 ? 16 : 64)) c = k > 1 ? 16 : 64;
     rpw = kBigRows * (int)c;
