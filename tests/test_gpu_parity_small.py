@@ -221,6 +221,8 @@ SEARCH_CASES = [
     (600, 40, 7, 2, torch.float16, "ip", False),        # E % 16 != 0: vector-ALU path on fp16
     (900, 64, 6, 2, torch.float16, "l2", False),
     (140000, 64, 40, 4, torch.float16, "ip", True),     # several row passes per workgroup
+    (70001, 256, 130, 1, torch.float16, "ip", True),    # large batch: three chunks per workgroup, ragged end
+    (66000, 512, 70, 2, torch.float16, "ip", True),     # large batch, widest rows, re-scored top-2
 ]
 
 
