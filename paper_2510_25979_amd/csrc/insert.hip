@@ -48,9 +48,12 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_kernel(const InsertAr
   const int il = lane & 31, kh = lane >> 5;
   const int S = a.S, g = a.Hq / a.Hkv;
 
-  // all row blocks of one (item, layer, head) get ids that are equal mod 8 (same XCD / L2)
+  // Workgroup ids that are equal mod 8 run on the same XCD and share its L2.  All row blocks of
+  // one (item, layer, head) AND all g heads that read the same K and V get such ids, so K and
+  // V come from HBM once per group: KV group (t / g) * 8 + x for the t-th tile slot of XCD x.
   const int bid = blockIdx.x;
-  const int tile = (bid >> 3) / a.n_rblk * 8 + (bid & 7);
+  const int x = bid & 7, t = (bid >> 3) / a.n_rblk;
+  const int tile = ((t / g) * 8 + x) * g + t % g;
   const int R = a.n_rblk - 1 - (bid >> 3) % a.n_rblk;
   if (tile >= a.n_tiles) return;
   const int h = tile % a.Hq;
@@ -265,8 +268,9 @@ hipError_t launch_insert(const InsertLaunch& p, hipStream_t stream) {
   a.n_tiles = p.B * p.Lc * p.Hq;
   const float scale = p.scale == 0.f ? 1.0f / sqrtf((float)p.D) : p.scale;
   a.scale_log2e = scale * 1.44269504088896340736f;
-  const int tiles8 = (a.n_tiles + 7) / 8 * 8;
-  const dim3 grid((unsigned)((size_t)tiles8 * a.n_rblk));
+  const int g = p.Hq / p.Hkv;
+  const int groups8 = (a.n_tiles / g + 7) / 8 * 8;   // KV groups, padded to a multiple of 8
+  const dim3 grid((unsigned)((size_t)groups8 * g * a.n_rblk));
   return p.D == 64 ? launch_insert_d<64>(a, grid, p.causal, p.packed, stream)
                    : launch_insert_d<128>(a, grid, p.causal, p.packed, stream);
 }
