@@ -379,10 +379,13 @@ __global__ __launch_bounds__(kThreads, 2) void exact_bf16_long_kernel(const Exac
   };
 
   // ---- this wave's 32 query rows, as the column operand of the first product
+  // (a wave whose rows lie beyond a ragged end works on a copy of the last row and stores
+  // nothing: the main loop below then needs no per-wave branch, whose merge would cost a copy
+  // of the accumulator per chunk)
   u32x4 q[D / 16];
-  if (active) {
+  {
     const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.Q) +
-                         (((size_t)b * a.Hq + h) * S + r0 + il) * D + 8 * kh;
+                         (((size_t)b * a.Hq + h) * S + min(r0 + il, S - 1)) * D + 8 * kh;
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks) q[ks] = *reinterpret_cast<const u32x4*>(qrow + 16 * ks);
   }
@@ -532,10 +535,10 @@ __global__ __launch_bounds__(kThreads, 2) void exact_bf16_long_kernel(const Exac
   for (; c + 1 < c_split; c += 2) {
     publish();
     prefetch(kb1, vb1, c + 1);
-    if (active) step(kb0, vb0, c, 2, false);
+    step(kb0, vb0, c, 2, false);
     publish();
     if (c + 2 < n_chunk) prefetch(kb0, vb0, c + 2);
-    if (active) step(kb1, vb1, c + 1, 2, false);
+    step(kb1, vb1, c + 1, 2, false);
   }
   // (one copy of the masked code: the stage is picked at run time, which only costs the
   // compiler its proof that copy and reads touch different arrays, i.e. some overlap)
