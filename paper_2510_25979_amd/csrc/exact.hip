@@ -1,10 +1,12 @@
 // Recompute branch of Algorithm 2: O = softmax(scale * Q K^T) V, causal or
 // dense, without ever writing the S x S map (flash-style online softmax).
 //
-// bf16 path (matrix cores, v_mfma_f32_32x32x16_bf16).  One workgroup = one
-// (batch item, KV head, block of 128 query rows); when the sequence fits one
-// block it walks all g query heads that share the K and V tile, so K and V are
-// staged once per group, and requests the next head's Q while it computes.
+// bf16 path (matrix cores, v_mfma_f32_32x32x16_bf16), one kernel in two variants:
+//   * resident (S <= 128): one workgroup = one (batch item, KV head); both 64-key chunks of K
+//     and V are copied into LDS once and the workgroup walks all g query heads that share
+//     them; after the one barrier behind the copy its four waves never meet again;
+//   * streaming (S > 128): one workgroup = one (batch item, query head, block of 128 query
+//     rows) that streams 64-key chunks of K and V through two LDS stages.
 // A wave owns 32 query rows and walks the key blocks up to its diagonal.
 // Both products are formed transposed:
 //   S^T = K Q^T   -> a lane holds 16 keys of ONE query column, so the row
@@ -15,10 +17,6 @@
 //                    goes from the first MFMA to the second without leaving
 //                    registers (the contraction slots are matched by reading
 //                    V^T from LDS in the same key order).
-// Causal work grows with the row block (1..4 key blocks), and wave i of every
-// workgroup runs on SIMD i: the wave -> row block assignment is therefore
-// rotated with the workgroup and head index so that all four SIMDs see the
-// same mix.  K is staged row-major, V transposed, 128 keys per LDS chunk.
 // Softmax runs in the log2 domain with the scale folded into one FMA per
 // score; the accumulator is rescaled only when some row maximum has moved far.
 #include "common.hpp"
@@ -26,13 +24,11 @@
 
 namespace ac {
 
-constexpr int kKPad = 8;   // elements of padding per staged K row (keeps 16-byte alignment)
 constexpr int kOPass = 64; // output columns staged per pass (16 rows at a time)
 constexpr int kOStride = kOPass + 4;
 // Online softmax: weights are 2^(score - m); m moves (and the accumulator is rescaled) only when
-// a row maximum has outgrown it by more than this many bits, see the long-sequence kernel.
+// a row maximum has outgrown it by more than this many bits (see the chunk step below).
 constexpr float kRescaleSlack = 8.0f;
-
 
 struct ExactArgs {
   const void *Q, *K, *V;
@@ -42,208 +38,11 @@ struct ExactArgs {
   int32_t heads_per_wg;
   int32_t n_rblk;
   int32_t n_kvtiles;
-  int32_t n_blocks;   // tiles of the short-sequence kernel (its grid may be smaller)
+  int32_t n_blocks;   // tiles of the launch (the grid of a routed resident launch is smaller)
   float scale_log2e;
 };
 
-template <int D, bool CAUSAL>
-__global__ __launch_bounds__(kThreads, (D == 64 ? 4 : 2)) void exact_bf16_kernel(const ExactArgs a) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int KS = D + kKPad;
-  bf16_t* ks_lds = reinterpret_cast<bf16_t*>(smem);
-  bf16_t* vt = ks_lds + kChunk * KS;
-  bf16_t* ost_all = vt + D * kVtStride;   // [4][16][kOStride], present only when heads_per_wg > 1
-
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
-  const int il = lane & 31, kh = lane >> 5;
-  const int S = a.S, g = a.Hq / a.Hkv;
-  // One tile per workgroup, or (when queries are routed, so that many tiles may have nothing
-  // to do) a fixed number of workgroups that each take every gridDim.x-th tile: skipping a
-  // tile then costs a scalar test instead of a workgroup launch.
-  bool first_tile = true;
-  for (int bid = blockIdx.x; bid < a.n_blocks; bid += gridDim.x) {
-    const int slot = bid >> 3;
-    const int hslots = g / a.heads_per_wg;
-    const int per_u = hslots * a.n_rblk;
-    const int u = (slot / per_u) * 8 + (bid & 7);
-    if (u >= a.n_kvtiles) continue;
-    const int h_first = ((slot % per_u) / a.n_rblk) * a.heads_per_wg;
-    const int R = a.n_rblk - 1 - (slot % per_u) % a.n_rblk;
-    const int b = u / a.Hkv, kvh = u % a.Hkv;
-    if (a.row_sel && a.row_sel[b] >= 0) continue;
-    if (!first_tile) __syncthreads();   // the previous tile's output staging used the same LDS
-    first_tile = false;
-
-    const bf16_t* Kt = reinterpret_cast<const bf16_t*>(a.K) + (size_t)u * S * D;
-    const bf16_t* Vt_src = reinterpret_cast<const bf16_t*>(a.V) + (size_t)u * S * D;
-    const int n_chunk = CAUSAL ? R + 1 : (S + kChunk - 1) / kChunk;
-    const int nrow32 = min(4, (S - R * kChunk) >> 5);
-    const int rot = slot & 3;
-
-    auto load_q = [&](int hl, u32x4 (&q)[D / 16]) {
-      const int rw = (wave + rot + hl) & 3;
-      if (rw < nrow32) {
-        const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.Q) +
-                             (((size_t)b * a.Hq + kvh * g + h_first + hl) * S + R * kChunk + 32 * rw + il) * D +
-                             8 * kh;
-#pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) q[ks] = *reinterpret_cast<const u32x4*>(qrow + 16 * ks);
-      }
-    };
-
-    u32x4 qreg[D / 16], qnext[D / 16];
-    load_q(0, qnext);
-
-    for (int hl = 0; hl < a.heads_per_wg; ++hl) {
-      const int h = kvh * g + h_first + hl;
-      const int rw = (wave + rot + hl) & 3;
-      const bool active = rw < nrow32;
-      const int r0 = R * kChunk + 32 * rw;
-#pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) qreg[ks] = qnext[ks];
-
-      f32x16 acc[D / 32];
-#pragma unroll
-      for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
-      float m_run = -INFINITY;
-      float l_run = 0.f;
-
-      for (int c = 0; c < n_chunk; ++c) {
-        const int j0 = c * kChunk;
-        const int nj = min(kChunk, S - j0);
-        if (hl == 0 || n_chunk > 1) {
-          if (c > 0 || hl > 0) __syncthreads();
-          constexpr int DQ = D / 8;
-          const u32x4* src = reinterpret_cast<const u32x4*>(Kt + (size_t)j0 * D);
-          for (int p = tid; p < nj * DQ; p += kThreads) {
-            const int j = p / DQ, dq = p % DQ;
-            *reinterpret_cast<u32x4*>(ks_lds + j * KS + 8 * dq) = src[p];
-          }
-          stage_v_transposed<D>(Vt_src + (size_t)j0 * D, nj, vt, tid);
-          __syncthreads();
-        }
-        if (c + 1 == n_chunk && hl + 1 < a.heads_per_wg) load_q(hl + 1, qnext);
-
-        if (active) {
-          int nblk = nj >> 5;
-          if (CAUSAL) nblk = min(nblk, (r0 - j0) / 32 + 1);
-          int jb = 0;
-          for (; jb < nblk; ++jb) {
-            f32x16 s;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) s[v] = 0.f;
-            const bf16_t* krow = ks_lds + (32 * jb + il) * KS + 8 * kh;
-#pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks)
-              s = mfma_bf16(*reinterpret_cast<const bf16x8*>(krow + 16 * ks),
-                            __builtin_bit_cast(bf16x8, qreg[ks]), s);
-            if (CAUSAL && j0 + 32 * jb == r0) {
-#pragma unroll
-              for (int v = 0; v < 16; ++v)
-                if (mfma_row(v, kh) > il) s[v] = -INFINITY;
-            }
-            float mx = s[0];
-#pragma unroll
-            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            // the reference point follows the row maximum with kRescaleSlack bits of slack
-            float m_new = m_run;
-            {
-              const float cand = fmaxf(m_run, mx * a.scale_log2e);
-              if (__any(cand > m_run + kRescaleSlack)) {
-                const float alpha = __builtin_amdgcn_exp2f(m_run - cand);
-                l_run *= alpha;
-#pragma unroll
-                for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-                  for (int v = 0; v < 16; ++v) acc[db][v] *= alpha;
-                m_run = m_new = cand;
-              }
-            }
-            float psum = 0.f;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              s[v] = __builtin_amdgcn_exp2f(fmaf(s[v], a.scale_log2e, -m_new));
-              psum += s[v];
-            }
-            l_run += psum;
-#pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-              u32x4 pw;
-              pw.x = pack_bf16(s[8 * s2 + 0], s[8 * s2 + 1]);
-              pw.y = pack_bf16(s[8 * s2 + 2], s[8 * s2 + 3]);
-              pw.z = pack_bf16(s[8 * s2 + 4], s[8 * s2 + 5]);
-              pw.w = pack_bf16(s[8 * s2 + 6], s[8 * s2 + 7]);
-              const bf16x8 pop = __builtin_bit_cast(bf16x8, pw);
-#pragma unroll
-              for (int db = 0; db < D / 32; ++db) {
-                const bf16_t* vrow = vt + (32 * db + il) * kVtStride + 32 * jb + 16 * s2 + 4 * kh;
-                u32x2 lo = *reinterpret_cast<const u32x2*>(vrow);
-                u32x2 hi = *reinterpret_cast<const u32x2*>(vrow + 8);
-                u32x4 w = {lo.x, lo.y, hi.x, hi.y};
-                acc[db] = mfma_bf16(__builtin_bit_cast(bf16x8, w), pop, acc[db]);
-              }
-            }
-          }
-        }
-      }
-
-      if (a.heads_per_wg == 1) __syncthreads();
-      if (active) {
-        const float inv = 1.0f / (l_run + __shfl_xor(l_run, 32));
-        bf16_t* Oh = reinterpret_cast<bf16_t*>(a.O) + (((size_t)b * a.Hq + h) * S + r0) * (size_t)D;
-        if (a.heads_per_wg == 1) {
-          // K is no longer needed: the whole 32 x D tile is staged on top of it and leaves as
-          // complete contiguous rows (measurably better than 64-byte row segments)
-          store_tile_bf16<D>(acc, inv, ks_lds + wave * (32 * (D + 4)), Oh, lane);
-        } else {
-          // K must survive for the next head: a small wave-private buffer takes 16 rows x 64
-          // columns per pass, so every global store still covers whole 128-byte lines
-          bf16_t* ost = ost_all + wave * (16 * kOStride);
-#pragma unroll
-          for (int rh = 0; rh < 2; ++rh)
-#pragma unroll
-            for (int dh = 0; dh < D / 64; ++dh) {
-              if ((il >> 4) == rh) {
-#pragma unroll
-                for (int dbp = 0; dbp < 2; ++dbp)
-#pragma unroll
-                  for (int vq = 0; vq < 4; ++vq) {
-                    const f32x16& t = acc[2 * dh + dbp];
-                    u32x2 w;
-                    w.x = pack_bf16(t[4 * vq] * inv, t[4 * vq + 1] * inv);
-                    w.y = pack_bf16(t[4 * vq + 2] * inv, t[4 * vq + 3] * inv);
-                    *reinterpret_cast<u32x2*>(ost + (il & 15) * kOStride + 32 * dbp + 8 * vq + 4 * kh) = w;
-                  }
-              }
-              __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-              __builtin_amdgcn_wave_barrier();
-              __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-              for (int it = 0; it < 2; ++it) {
-                const int p = it * kWave + lane;
-                const int row = p >> 3, c8 = p & 7;
-                const u32x2* sp = reinterpret_cast<const u32x2*>(ost + row * kOStride + 8 * c8);
-                u32x2 lo = sp[0], hi = sp[1];
-                __builtin_nontemporal_store(
-                    u32x4{lo.x, lo.y, hi.x, hi.y},
-                    reinterpret_cast<u32x4*>(Oh + (size_t)(16 * rh + row) * D + 64 * dh + 8 * c8));
-              }
-              __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-              __builtin_amdgcn_wave_barrier();
-            }
-        }
-      }
-    }
-  }
-}
-
-// Long sequences (S > 128): one workgroup = one (batch item, query head, block of 128 query
-// rows) that walks the keys in chunks of 64.  Same transposed products and in-register P as
-// above; what differs is how K and V reach the matrix cores:
+// How K and V reach the matrix cores:
 //   * each chunk of K and of V is copied global -> LDS directly (global_load_lds_dwordx4, no
 //     data registers, no ALU work), row-major, into one of two stages, so the copy of chunk
 //     c + 1 is in flight while chunk c is multiplied and one barrier per chunk suffices;
@@ -253,8 +52,8 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 4 : 2)) void exact_bf16_kernel
 //   * the V^T operand is fetched with the transposing LDS read (ds_read_b64_tr_b16): in a
 //     group of 16 lanes, lane i names four consecutive d of key j(i / 4) and lane t receives,
 //     for its own d, the four keys j(0..3);
-//   * the two 32-key blocks of a chunk share one softmax step (one maximum exchange, one
-//     rescale test per 64 keys), which also gives the scheduler two independent chains.
+//   * the two 32-key blocks of a chunk take their softmax steps in an order that lets matrix
+//     and vector work of one wave overlap (see the chunk step below).
 constexpr int kLChunk = 64;
 
 // max(x[l], x[l ^ 32]) in every lane l.  v_permlane32_swap_b32 exchanges the upper 32 lanes of
@@ -275,8 +74,8 @@ __host__ __device__ constexpr int k_piece_swizzle(int r) {
   return D == 128 ? (r & 15) : ((r >> 1) & 7);
 }
 
-template <int D, bool CAUSAL>
-__global__ __launch_bounds__(kThreads, 2) void exact_bf16_long_kernel(const ExactArgs a) {
+template <int D, bool CAUSAL, bool RESIDENT>
+__global__ __launch_bounds__(kThreads, 2) void exact_bf16_kernel(const ExactArgs a) {
   constexpr int PPR = D / 8;                          // 16-byte pieces per row
   constexpr int NCOPY = kLChunk * PPR / kWave / 4;    // copy instructions per wave, tensor, chunk
   constexpr int kVSwz = PPR / 2 - 1;
@@ -284,29 +83,23 @@ __global__ __launch_bounds__(kThreads, 2) void exact_bf16_long_kernel(const Exac
   __shared__ __attribute__((aligned(16))) bf16_t vb0[kLChunk * D];
   __shared__ __attribute__((aligned(16))) bf16_t kb1[kLChunk * D];
   __shared__ __attribute__((aligned(16))) bf16_t vb1[kLChunk * D];
+  // wave-private output staging of the resident mode (16 rows x 64 columns per pass)
+  __shared__ __attribute__((aligned(16))) bf16_t ost_small[4 * 16 * kOStride];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
   const int il = lane & 31, kh = lane >> 5;
   const int S = a.S, g = a.Hq / a.Hkv;
-  const int bid = blockIdx.x;
-  const int slot = bid >> 3;
-  const int per_u = g * a.n_rblk;
-  const int u = (slot / per_u) * 8 + (bid & 7);
-  if (u >= a.n_kvtiles) return;
-  const int h = (u % a.Hkv) * g + (slot % per_u) / a.n_rblk;
-  const int R = a.n_rblk - 1 - (slot % per_u) % a.n_rblk;   // heaviest row blocks first
-  const int b = u / a.Hkv;
-  if (a.row_sel && a.row_sel[b] >= 0) return;
+  // Sequences of up to 128 keys are RESIDENT: both 64-key chunks of K and V sit in the two
+  // stages for the whole tile, the workgroup walks all heads_per_wg query heads that share
+  // them, and between the one barrier after the copy and the end of the tile the four waves
+  // never meet again.  Longer sequences stream chunks through the stages, one head per tile.
 
-  const bf16_t* Ksrc = reinterpret_cast<const bf16_t*>(a.K) + (size_t)u * S * D;
-  const bf16_t* Vsrc = reinterpret_cast<const bf16_t*>(a.V) + (size_t)u * S * D;
-  const int last_key = CAUSAL ? min(S, kChunk * (R + 1)) : S;
-  const int n_chunk = (last_key + kLChunk - 1) / kLChunk;
-  const int rw = wave;
-  const int r0 = R * kChunk + 32 * rw;
-  const bool active = r0 < S;
-
+  // per tile (the helpers below read these by reference)
+  int u = 0, h = 0, R = 0, b = 0, r0 = 0, n_chunk = 0;
+  bool active = false;
+  const bf16_t* Ksrc = nullptr;
+  const bf16_t* Vsrc = nullptr;
 
   // ---- copies: instruction k = wave + 4 i fills LDS slots [64 k, 64 k + 64), slot = row * PPR +
   // position.  From one instruction to the next, row grows by 256 / PPR (which leaves both
@@ -317,8 +110,8 @@ __global__ __launch_bounds__(kThreads, 2) void exact_bf16_long_kernel(const Exac
   const int vpiece = cpos ^ (2 * (crow & kVSwz));
   // Running source pointers, one per tensor, advanced by one chunk after each use (cheaper
   // than rebuilding 64-bit addresses from the chunk index every time).
-  const bf16_t* kptr = Ksrc + crow * D + 8 * kpiece;
-  const bf16_t* vptr = Vsrc + crow * D + 8 * vpiece;
+  const bf16_t* kptr = nullptr;   // set per tile
+  const bf16_t* vptr = nullptr;
   auto prefetch = [&](bf16_t* kb, bf16_t* vb, int c) {
     const int nj = min(kLChunk, S - c * kLChunk);
     if (nj == kLChunk) {
@@ -378,24 +171,25 @@ __global__ __launch_bounds__(kThreads, 2) void exact_bf16_long_kernel(const Exac
     return __builtin_bit_cast(bf16x8, w);
   };
 
-  // ---- this wave's 32 query rows, as the column operand of the first product
-  // (a wave whose rows lie beyond a ragged end works on a copy of the last row and stores
-  // nothing: the main loop below then needs no per-wave branch, whose merge would cost a copy
-  // of the accumulator per chunk)
   u32x4 q[D / 16];
-  {
+  f32x16 acc[D / 32];
+  float m_run = -INFINITY, l_run = 0.f;
+  // this wave's 32 query rows of head h as the column operand of the first product, and a
+  // fresh accumulator.  (A wave whose rows lie beyond a ragged end works on a copy of the last
+  // row and stores nothing: the streaming loop then needs no per-wave branch, whose merge
+  // would cost a copy of the accumulator per chunk.)
+  auto begin_head = [&]() {
     const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.Q) +
                          (((size_t)b * a.Hq + h) * S + min(r0 + il, S - 1)) * D + 8 * kh;
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks) q[ks] = *reinterpret_cast<const u32x4*>(qrow + 16 * ks);
-  }
-
-  f32x16 acc[D / 32];
 #pragma unroll
-  for (int db = 0; db < D / 32; ++db)
+    for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+      for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+    m_run = -INFINITY;
+    l_run = 0.f;
+  };
 
   // ---- pieces of one chunk step (32-key block jb of the stage)
   // scores^T of block jb: 32 keys x 32 query rows, this lane: query row il, 16 of the keys
@@ -525,37 +319,127 @@ __global__ __launch_bounds__(kThreads, 2) void exact_bf16_long_kernel(const Exac
     __syncthreads();
   };
 
-  // Chunks below c_split are complete and fully visible to every wave of the workgroup (they
-  // lie left of the diagonal blocks of all 128 rows, and before a ragged end): the main loop
-  // runs only the test-free variant, two chunks per trip so that stages alternate without
-  // pointer arithmetic.  The few chunks from c_split on go through the masked variant.
-  const int c_split = CAUSAL ? min(2 * R, S / kLChunk) : S / kLChunk;
-  prefetch(kb0, vb0, 0);
-  int c = 0;
-  for (; c + 1 < c_split; c += 2) {
-    publish();
-    prefetch(kb1, vb1, c + 1);
-    step(kb0, vb0, c, 2, false);
-    publish();
-    if (c + 2 < n_chunk) prefetch(kb0, vb0, c + 2);
-    step(kb1, vb1, c + 1, 2, false);
-  }
-  // (one copy of the masked code: the stage is picked at run time, which only costs the
-  // compiler its proof that copy and reads touch different arrays, i.e. some overlap)
-  for (; c < n_chunk; ++c) {
-    publish();
-    bf16_t* kcur = (c & 1) ? kb1 : kb0;
-    bf16_t* vcur = (c & 1) ? vb1 : vb0;
-    if (c + 1 < n_chunk) prefetch((c & 1) ? kb0 : kb1, (c & 1) ? vb0 : vb1, c + 1);
-    tail_step(kcur, vcur, c);
-  }
-  __syncthreads();   // every wave is done with both stages: they now stage the output
-  if (active) {
-    const float inv = 1.0f / (l_run + __shfl_xor(l_run, 32));
-    bf16_t* Oh = reinterpret_cast<bf16_t*>(a.O) + (((size_t)b * a.Hq + h) * S + r0) * (size_t)D;
-    bf16_t* ost = wave == 0 ? kb0 : wave == 1 ? vb0 : wave == 2 ? kb1 : vb1;
-    store_tile_bf16<D>(acc, inv, ost, Oh, lane);
-  }
+  // the 32 x D result of this wave in 16 x 64 passes through its small private buffer (the
+  // stages still hold K and V for the next head); every global store covers whole 128-byte lines
+  auto store_small = [&](bf16_t* Oh, float inv) {
+    bf16_t* ost = ost_small + wave * (16 * kOStride);
+#pragma unroll
+    for (int rh = 0; rh < 2; ++rh)
+#pragma unroll
+      for (int dh = 0; dh < D / 64; ++dh) {
+        if ((il >> 4) == rh) {
+#pragma unroll
+          for (int dbp = 0; dbp < 2; ++dbp)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+              const f32x16& t = acc[2 * dh + dbp];
+              u32x2 w;
+              w.x = pack_bf16(t[4 * vq] * inv, t[4 * vq + 1] * inv);
+              w.y = pack_bf16(t[4 * vq + 2] * inv, t[4 * vq + 3] * inv);
+              *reinterpret_cast<u32x2*>(ost + (il & 15) * kOStride + 32 * dbp + 8 * vq + 4 * kh) = w;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+          const int p = it * kWave + lane;
+          const int row = p >> 3, c8 = p & 7;
+          const u32x2* sp = reinterpret_cast<const u32x2*>(ost + row * kOStride + 8 * c8);
+          u32x2 lo = sp[0], hi = sp[1];
+          __builtin_nontemporal_store(
+              u32x4{lo.x, lo.y, hi.x, hi.y},
+              reinterpret_cast<u32x4*>(Oh + (size_t)(16 * rh + row) * D + 64 * dh + 8 * c8));
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+      }
+  };
+
+  // One tile per workgroup, or (when queries are routed, so that many tiles may have nothing
+  // to do) a fixed number of workgroups that each take every gridDim.x-th tile: skipping a
+  // tile then costs a scalar test instead of a workgroup launch.
+  bool first_tile = true;
+  int bid = blockIdx.x;
+  do {   // a loop in the resident variant only (the condition below is constant otherwise)
+    const int slot = bid >> 3;
+    const int hslots = g / a.heads_per_wg;
+    const int per_u = hslots * a.n_rblk;
+    u = (slot / per_u) * 8 + (bid & 7);   // ids equal mod 8 (one XCD) share K, V in its L2
+    if (u >= a.n_kvtiles) continue;
+    const int h_first = (u % a.Hkv) * g + ((slot % per_u) / a.n_rblk) * a.heads_per_wg;
+    R = a.n_rblk - 1 - (slot % per_u) % a.n_rblk;   // heaviest row blocks first
+    b = u / a.Hkv;
+    if (a.row_sel && a.row_sel[b] >= 0) continue;
+    if (!first_tile) __syncthreads();   // the previous tile may still be read or staged in LDS
+    first_tile = false;
+    Ksrc = reinterpret_cast<const bf16_t*>(a.K) + (size_t)u * S * D;
+    Vsrc = reinterpret_cast<const bf16_t*>(a.V) + (size_t)u * S * D;
+    kptr = Ksrc + crow * D + 8 * kpiece;
+    vptr = Vsrc + crow * D + 8 * vpiece;
+    const int last_key = CAUSAL ? min(S, kChunk * (R + 1)) : S;
+    n_chunk = (last_key + kLChunk - 1) / kLChunk;
+
+    if (RESIDENT) {
+      prefetch(kb0, vb0, 0);
+      if (n_chunk > 1) prefetch(kb1, vb1, 1);
+      publish();
+      const int rot = slot & 3;
+      for (int hl = 0; hl < a.heads_per_wg; ++hl) {
+        h = h_first + hl;
+        // causal work grows with the row block and wave i always runs on SIMD i: rotating the
+        // wave -> row block assignment lets every SIMD see the same mix
+        r0 = 32 * ((wave + rot + hl) & 3);
+        active = r0 < S;
+        begin_head();
+        for (int c = 0; c < n_chunk; ++c) tail_step(c ? kb1 : kb0, c ? vb1 : vb0, c);
+        if (a.heads_per_wg == 1) break;   // stored below, through the (now dead) stages
+        if (active) {
+          const float inv = 1.0f / (l_run + __shfl_xor(l_run, 32));
+          store_small(reinterpret_cast<bf16_t*>(a.O) + (((size_t)b * a.Hq + h) * S + r0) * (size_t)D, inv);
+        }
+      }
+      if (a.heads_per_wg > 1) continue;
+    } else {
+      h = h_first;
+      r0 = R * kChunk + 32 * wave;
+      active = r0 < S;
+      begin_head();
+      // Chunks below c_split are complete and fully visible to every wave of the workgroup
+      // (they lie left of the diagonal blocks of all 128 rows, and before a ragged end): the
+      // main loop runs only the test-free variant, two chunks per trip so that stages
+      // alternate without pointer arithmetic.  The few chunks from c_split on go through the
+      // masked variant.
+      const int c_split = CAUSAL ? min(2 * R, S / kLChunk) : S / kLChunk;
+      prefetch(kb0, vb0, 0);
+      int c = 0;
+      for (; c + 1 < c_split; c += 2) {
+        publish();
+        prefetch(kb1, vb1, c + 1);
+        step(kb0, vb0, c, 2, false);
+        publish();
+        if (c + 2 < n_chunk) prefetch(kb0, vb0, c + 2);
+        step(kb1, vb1, c + 1, 2, false);
+      }
+      // (one copy of the masked code: the stage is picked at run time, which only costs the
+      // compiler its proof that copy and reads touch different arrays, i.e. some overlap)
+      for (; c < n_chunk; ++c) {
+        publish();
+        bf16_t* kcur = (c & 1) ? kb1 : kb0;
+        bf16_t* vcur = (c & 1) ? vb1 : vb0;
+        if (c + 1 < n_chunk) prefetch((c & 1) ? kb0 : kb1, (c & 1) ? vb0 : vb1, c + 1);
+        tail_step(kcur, vcur, c);
+      }
+    }
+    __syncthreads();   // every wave is done with both stages: they now stage the output
+    if (active) {
+      const float inv = 1.0f / (l_run + __shfl_xor(l_run, 32));
+      bf16_t* Oh = reinterpret_cast<bf16_t*>(a.O) + (((size_t)b * a.Hq + h) * S + r0) * (size_t)D;
+      bf16_t* ost = wave == 0 ? kb0 : wave == 1 ? vb0 : wave == 2 ? kb1 : vb1;
+      store_tile_bf16<D>(acc, inv, ost, Oh, lane);
+    }
+  } while (RESIDENT && (bid += gridDim.x) < a.n_blocks);
 }
 
 // fp32 path (vector ALUs): one wave per (batch item, head, query row).
@@ -598,29 +482,21 @@ __global__ __launch_bounds__(kWave) void exact_f32_kernel(const ExactArgs a, int
   }
 }
 
-static size_t exact_lds_bytes(int D, int heads_per_wg) {
-  const size_t kv = (size_t)(kChunk * (D + kKPad) + D * kVtStride) * sizeof(bf16_t);
-  return heads_per_wg > 1 ? kv + (size_t)4 * 16 * kOStride * sizeof(bf16_t) : kv;
-}
-
-template <int D, bool CAUSAL>
-static hipError_t launch_exact_bf16(ExactArgs a, dim3 grid, hipStream_t stream) {
+template <int D, bool CAUSAL, bool RESIDENT>
+static hipError_t launch_exact_bf16_r(ExactArgs a, dim3 grid, hipStream_t stream) {
   a.n_blocks = (int32_t)grid.x;
   // routed launch: 32 workgroups per compute unit walk the tiles (enough of them for the
   // hardware to even out an uneven mix of hits and misses; a multiple of 8 keeps the
   // tile -> XCD assignment of the one-tile-per-workgroup launch)
-  if (a.row_sel && grid.x > 8192u) grid.x = 8192u;
-  const size_t lds = exact_lds_bytes(D, a.heads_per_wg);
-  hipError_t e = ensure_lds<&exact_bf16_kernel<D, CAUSAL>>(lds);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((exact_bf16_kernel<D, CAUSAL>), grid, dim3(kThreads), lds, stream, a);
+  if (RESIDENT && a.row_sel && grid.x > 8192u) grid.x = 8192u;
+  hipLaunchKernelGGL((exact_bf16_kernel<D, CAUSAL, RESIDENT>), grid, dim3(kThreads), 0, stream, a);
   return hipGetLastError();
 }
 
 template <int D, bool CAUSAL>
-static hipError_t launch_exact_long(const ExactArgs& a, dim3 grid, hipStream_t stream) {
-  hipLaunchKernelGGL((exact_bf16_long_kernel<D, CAUSAL>), grid, dim3(kThreads), 0, stream, a);
-  return hipGetLastError();
+static hipError_t launch_exact_bf16(const ExactArgs& a, dim3 grid, hipStream_t stream) {
+  return a.n_rblk == 1 ? launch_exact_bf16_r<D, CAUSAL, true>(a, grid, stream)
+                       : launch_exact_bf16_r<D, CAUSAL, false>(a, grid, stream);
 }
 
 hipError_t launch_exact(const ExactLaunch& p, hipStream_t stream) {
@@ -643,13 +519,6 @@ hipError_t launch_exact(const ExactLaunch& p, hipStream_t stream) {
   a.heads_per_wg = a.n_rblk == 1 ? g : 1;
   const int u8 = (a.n_kvtiles + 7) / 8 * 8;
   const dim3 grid((unsigned)((size_t)u8 * (g / a.heads_per_wg) * a.n_rblk));
-  if (a.n_rblk > 1) {   // long rows: chunked walk with direct global -> LDS copies
-    if (p.D == 64)
-      return p.causal ? launch_exact_long<64, true>(a, grid, stream)
-                      : launch_exact_long<64, false>(a, grid, stream);
-    return p.causal ? launch_exact_long<128, true>(a, grid, stream)
-                    : launch_exact_long<128, false>(a, grid, stream);
-  }
   if (p.D == 64)
     return p.causal ? launch_exact_bf16<64, true>(a, grid, stream)
                     : launch_exact_bf16<64, false>(a, grid, stream);
