@@ -90,6 +90,17 @@ __global__ __launch_bounds__(kThreads, 2) void exact_bf16_kernel(const ExactArgs
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
   const int il = lane & 31, kh = lane >> 5;
   const int S = a.S, g = a.Hq / a.Hkv;
+  if (RESIDENT && a.row_sel) {
+    // routed launch: leave at once when none of this workgroup's tiles has anything to do (a
+    // batch that was served entirely by the reuse branch then costs a few scalar loads)
+    bool any = false;
+    const int per_u = (g / a.heads_per_wg) * a.n_rblk;
+    for (int t = blockIdx.x; t < a.n_blocks && !any; t += gridDim.x) {
+      const int ut = ((t >> 3) / per_u) * 8 + (t & 7);
+      any = ut < a.n_kvtiles && a.row_sel[ut / a.Hkv] < 0;
+    }
+    if (!any) return;
+  }
   // Sequences of up to 128 keys are RESIDENT: both 64-key chunks of K and V sit in the two
   // stages for the whole tile, the workgroup walks all heads_per_wg query heads that share
   // them, and between the one barrier after the copy and the end of the tile the four waves
