@@ -75,7 +75,7 @@ __host__ __device__ constexpr int k_piece_swizzle(int r) {
 }
 
 template <int D, bool CAUSAL, bool RESIDENT>
-__global__ __launch_bounds__(kThreads, 2) void exact_bf16_kernel(const ExactArgs a) {
+__global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel(const ExactArgs a) {
   constexpr int PPR = D / 8;                          // 16-byte pieces per row
   constexpr int NCOPY = kLChunk * PPR / kWave / 4;    // copy instructions per wave, tensor, chunk
   constexpr int kVSwz = PPR / 2 - 1;
