@@ -39,6 +39,8 @@ def lib():
         L.oracle_attention_exact.argtypes = [vp, vp, vp, vp, vp, vp] + [i32] * 6 + [f64]
         L.oracle_round_maps.restype = i32
         L.oracle_round_maps.argtypes = [vp, vp, i64, i32]
+        L.oracle_project.restype = i32
+        L.oracle_project.argtypes = [vp] * 7 + [i32] * 6
         L.oracle_threads.restype = i32
         L.oracle_threads.argtypes = []
         _lib = L
@@ -122,4 +124,23 @@ def round_maps(P, kind=ROUND_BF16):
     P = np.ascontiguousarray(np.asarray(P, dtype=np.float64))
     out = np.empty(P.shape, np.float32)
     _check(lib().oracle_round_maps(_p(P), _p(out), P.size, kind), "oracle_round_maps")
+    return out
+
+
+def project(h, W1, b1, W2, b2, seq_len=None, normalize=True):
+    """Feature projector.  h[B,S,dm], W1[hid,dm], b1[hid]|None, W2[E,hid], b2[E]|None -> f[B,E] float64."""
+    h, W1, W2 = _f32(h), _f32(W1), _f32(W2)
+    B, S, dm = h.shape
+    hid, dm2 = W1.shape
+    E, hid2 = W2.shape
+    if dm != dm2 or hid != hid2:
+        raise ValueError("weight shapes disagree with the input")
+    b1 = None if b1 is None else _f32(b1)
+    b2 = None if b2 is None else _f32(b2)
+    if (b1 is not None and b1.shape != (hid,)) or (b2 is not None and b2.shape != (E,)):
+        raise ValueError("bias shapes disagree with the weights")
+    sl = None if seq_len is None else _i32(seq_len)
+    out = np.empty((B, E), np.float64)
+    _check(lib().oracle_project(_p(h), _p(sl), _p(W1), _p(b1), _p(W2), _p(b2), _p(out),
+                                B, S, dm, hid, E, int(bool(normalize))), "oracle_project")
     return out

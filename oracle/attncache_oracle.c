@@ -29,6 +29,9 @@
  *   oracle_round_maps       the storage step of database building (Fig. 3,
  *                           step 3): a computed map is rounded once to the
  *                           database's element type.
+ *   oracle_project          Algorithm 1, the feature_projector step: the
+ *                           two-layer MLP of Sec. 3.1 ("Feature Projector")
+ *                           on the mean-pooled hidden states.
  *
  * Parity pins: every routine here is pinned by the CPU tests (closed forms,
  * invariants, brute force, library cross-checks).  None is "parity unpinned".
@@ -288,6 +291,72 @@ int32_t oracle_round_maps(const double *P, float *out, int64_t count,
     out[i] = (kind == ORACLE_ROUND_BF16) ? (float)round_to_bf16(P[i])
                                          : (float)P[i];
   return ORACLE_OK;
+}
+
+/* --------------------------------------------------------- feature projector */
+
+/*
+ * Algorithm 1, the feature_projector step: the input embedding h of a
+ * sentence (its hidden states, one row of width dm per token) becomes the
+ * feature vector that is searched for.  Sec. 3.1 ("Feature Projector") fixes
+ * the network as two MLP layers that lower the dimension; it does not print
+ * the pooling, the activation or the normalisation, so this oracle states the
+ * reading the GPU library documents:
+ *
+ *   x[i]   = (1 / s) * sum_{t < s} h[t][i]                 mean over the s valid tokens
+ *   u[j]   = max(0, b1[j] + sum_i W1[j][i] * x[i])         first layer, ReLU
+ *   f[e]   = b2[e] + sum_j W2[e][j] * u[j]                 second layer
+ *   f      = f / ||f||_2  if normalize (left as is when the norm is 0)
+ *
+ * h[B][S][dm], seq_len[B] (NULL: every sentence has S tokens), W1[hid][dm],
+ * b1[hid] (NULL: zeros), W2[E][hid], b2[E] (NULL: zeros), out[B][E] double.
+ */
+int32_t oracle_project(const float *h, const int32_t *seq_len, const float *W1,
+                       const float *b1, const float *W2, const float *b2,
+                       double *out, int32_t B, int32_t S, int32_t dm,
+                       int32_t hid, int32_t E, int32_t normalize) {
+  if (!h || !W1 || !W2 || !out) return ORACLE_ERR_ARG;
+  if (B < 0 || S <= 0 || dm <= 0 || hid <= 0 || E <= 0) return ORACLE_ERR_ARG;
+  for (int32_t b = 0; b < B; ++b)
+    if (seq_len && (seq_len[b] < 1 || seq_len[b] > S)) return ORACLE_ERR_INDEX;
+  int32_t status = ORACLE_OK;
+#pragma omp parallel for schedule(static)
+  for (int32_t b = 0; b < B; ++b) {
+    double *x = (double *)malloc(sizeof(double) * (size_t)dm);
+    double *u = (double *)malloc(sizeof(double) * (size_t)hid);
+    if (!x || !u) {
+      status = ORACLE_ERR_NOMEM;
+    } else {
+      const int32_t s = seq_len ? seq_len[b] : S;
+      for (int32_t i = 0; i < dm; ++i) {
+        double sum = 0.0;
+        for (int32_t t = 0; t < s; ++t)
+          sum += (double)h[((size_t)b * S + t) * dm + i];
+        x[i] = sum / (double)s;
+      }
+      for (int32_t j = 0; j < hid; ++j) {
+        double sum = b1 ? (double)b1[j] : 0.0;
+        for (int32_t i = 0; i < dm; ++i)
+          sum += (double)W1[(size_t)j * dm + i] * x[i];
+        u[j] = sum > 0.0 ? sum : 0.0;
+      }
+      double norm2 = 0.0;
+      for (int32_t e = 0; e < E; ++e) {
+        double sum = b2 ? (double)b2[e] : 0.0;
+        for (int32_t j = 0; j < hid; ++j)
+          sum += (double)W2[(size_t)e * hid + j] * u[j];
+        out[(size_t)b * E + e] = sum;
+        norm2 += sum * sum;
+      }
+      if (normalize && norm2 > 0.0) {
+        const double inv = 1.0 / sqrt(norm2);
+        for (int32_t e = 0; e < E; ++e) out[(size_t)b * E + e] *= inv;
+      }
+    }
+    free(x);
+    free(u);
+  }
+  return status;
 }
 
 /* Number of OpenMP threads a parallel region will use (1 without OpenMP);
