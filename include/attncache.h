@@ -300,6 +300,50 @@ int32_t attncache_cache_stats(const attncache_db *db, uint64_t *lookups,
  * used on. */
 int32_t attncache_cache_reset(attncache_db *db);
 
+/*
+ * Feature projector (Algorithm 1: f = feature_projector(h); Sec. 3.1
+ * "Feature Projector": two MLP layers that map the input embedding to a
+ * feature vector of lower dimension).  The step in front of
+ * attncache_search: its output is a query block, or, for database building,
+ * the `feat` argument of attncache_insert.  The paper fixes the two layers;
+ * the pooling over tokens, the activation and the normalisation are this
+ * library's reading:
+ *
+ *   x[b]    = mean of h[b][t] over the sentence's tokens t < seq_len[b]
+ *   u[b]    = max(0, W1 x[b] + b1)
+ *   f[b]    = W2 u[b] + b2,   divided by its Euclidean norm when `normalize`
+ *             (a zero vector stays zero)
+ *
+ * All arithmetic is binary32 (fp32 matrix cores for the two layers).
+ *
+ *   h          DEVICE [B][S][model_dim], h_dtype AC_BF16 or AC_F32.
+ *   seq_len    NULL (every sentence has S tokens) or DEVICE [B] int32; values
+ *              are clamped to [1, S].  Tokens at and after seq_len[b] are not
+ *              read.
+ *   W1, b1     DEVICE fp32 [hidden_dim][model_dim] and [hidden_dim]
+ *              (row j holds the weights of hidden unit j); b1 may be NULL.
+ *   W2, b2     DEVICE fp32 [emb_dim][hidden_dim] and [emb_dim]; b2 may be NULL.
+ *   feat       DEVICE [B][emb_dim], feat_dtype AC_F16 or AC_F32 (rounded to
+ *              nearest even once, after normalisation).
+ *   model_dim, hidden_dim, emb_dim   multiples of 8; emb_dim <= 2048;
+ *              B <= 65535 (AC_ERR_SHAPE otherwise).  B == 0 is a no-op.
+ *   workspace  DEVICE, at least attncache_project_workspace_bytes(...) bytes
+ *              (0 is returned for non-positive sizes), 16-byte aligned;
+ *              contents are scratch.  AC_ERR_WORKSPACE if too small.
+ *
+ * Four launches on `stream`; deterministic (partial sums are added in a fixed
+ * order).  Weights and inputs are only read.
+ */
+size_t attncache_project_workspace_bytes(int32_t B, int32_t model_dim,
+                                         int32_t hidden_dim, int32_t emb_dim);
+int32_t attncache_project(const void *h, const int32_t *seq_len,
+                          const float *W1, const float *b1, const float *W2,
+                          const float *b2, void *feat, int32_t B, int32_t S,
+                          int32_t model_dim, int32_t hidden_dim,
+                          int32_t emb_dim, int32_t h_dtype, int32_t feat_dtype,
+                          int32_t normalize, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
 /* Short constant description of a status code. */
 const char *attncache_status_string(int32_t status);
 

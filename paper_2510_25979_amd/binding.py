@@ -27,7 +27,8 @@ _DTYPE_CODE = {torch.float32: AC_F32, torch.float16: AC_F16, torch.bfloat16: AC_
 SYMBOLS = ["attncache_workspace_bytes", "attncache_map_entry_bytes", "attncache_pack_maps",
            "attncache_build_db", "attncache_destroy_db",
            "attncache_search", "attncache_apply", "attention_exact", "attncache_insert",
-           "attncache_cache_stats", "attncache_cache_reset", "attncache_status_string",
+           "attncache_cache_stats", "attncache_cache_reset",
+           "attncache_project_workspace_bytes", "attncache_project", "attncache_status_string",
            "attncache_last_hip_error", "attncache_version"]
 
 
@@ -85,6 +86,10 @@ def lib():
         L.attncache_cache_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
         L.attncache_cache_reset.restype = i32
         L.attncache_cache_reset.argtypes = [vp]
+        L.attncache_project_workspace_bytes.restype = sz
+        L.attncache_project_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.attncache_project.restype = i32
+        L.attncache_project.argtypes = [vp] * 7 + [i32] * 8 + [vp, sz, vp]
         L.attncache_status_string.restype = ctypes.c_char_p
         L.attncache_status_string.argtypes = [i32]
         L.attncache_last_hip_error.restype = i32
@@ -307,3 +312,35 @@ def attention_exact(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, O: torch.
     rp = None if row_sel is None else _dev(row_sel, "row_sel", torch.int32, (B,))
     _check(lib().attention_exact(qp, kp, vp, op, rp, B, Hq, Hkv, S, D, _DTYPE_CODE[Q.dtype],
                                  int(causal), float(scale), _stream(stream)), "attention_exact")
+
+
+def attncache_project_workspace_bytes(B: int, model_dim: int, hidden_dim: int, emb_dim: int) -> int:
+    return int(lib().attncache_project_workspace_bytes(B, model_dim, hidden_dim, emb_dim))
+
+
+def attncache_project(h: torch.Tensor, W1: torch.Tensor, b1: Optional[torch.Tensor],
+                      W2: torch.Tensor, b2: Optional[torch.Tensor], feat: torch.Tensor,
+                      workspace: torch.Tensor, *, seq_len: Optional[torch.Tensor] = None,
+                      normalize: bool = True, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """h [B,S,dm] bf16|f32; W1 [hid,dm], b1 [hid], W2 [E,hid], b2 [E] f32; feat [B,E] f16|f32."""
+    if h.dim() != 3 or W1.dim() != 2 or W2.dim() != 2:
+        raise ValueError("h must be [B,S,dm], W1 [hid,dm], W2 [E,hid]")
+    B, S, dm = h.shape
+    hid, E = W1.shape[0], W2.shape[0]
+    if h.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("h must be bf16 or f32")
+    if feat.dtype not in (torch.float16, torch.float32):
+        raise ValueError("feat must be f16 or f32")
+    f32 = torch.float32
+    hp = _dev(h, "h")
+    w1 = _dev(W1, "W1", f32, (hid, dm))
+    w2 = _dev(W2, "W2", f32, (E, hid))
+    b1p = None if b1 is None else _dev(b1, "b1", f32, (hid,))
+    b2p = None if b2 is None else _dev(b2, "b2", f32, (E,))
+    fp = _dev(feat, "feat", None, (B, E))
+    sp = None if seq_len is None else _dev(seq_len, "seq_len", torch.int32, (B,))
+    wp = _dev(workspace, "workspace")
+    _check(lib().attncache_project(hp, sp, w1, b1p, w2, b2p, fp, B, S, dm, hid, E,
+                                   _DTYPE_CODE[h.dtype], _DTYPE_CODE[feat.dtype], int(normalize),
+                                   wp, workspace.numel() * workspace.element_size(),
+                                   _stream(stream)), "attncache_project")

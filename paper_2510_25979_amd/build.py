@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libattncache.so")
-SOURCES = ["api.hip", "apply.hip", "exact.hip", "insert.hip", "search.hip"]
+SOURCES = ["api.hip", "apply.hip", "exact.hip", "insert.hip", "project.hip", "search.hip"]
 HEADERS = ["common.hpp", "launch.hpp", os.path.join("..", "..", "include", "attncache.h")]
 
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 instructions

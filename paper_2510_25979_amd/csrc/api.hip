@@ -404,4 +404,38 @@ int32_t attncache_insert(attncache_db* db, const void* feat, const int32_t* slot
   return e == hipSuccess ? AC_OK : hip_fail(e);
 }
 
+size_t attncache_project_workspace_bytes(int32_t B, int32_t model_dim, int32_t hidden_dim,
+                                         int32_t emb_dim) {
+  if (B < 1 || model_dim < 1 || hidden_dim < 1 || emb_dim < 1) return 0;
+  return ac::project_workspace_bytes(B, model_dim, hidden_dim, emb_dim);
+}
+
+int32_t attncache_project(const void* h, const int32_t* seq_len, const float* W1, const float* b1,
+                          const float* W2, const float* b2, void* feat, int32_t B, int32_t S,
+                          int32_t model_dim, int32_t hidden_dim, int32_t emb_dim, int32_t h_dtype,
+                          int32_t feat_dtype, int32_t normalize, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  if (B < 0 || B > 65535 || S < 1 || model_dim < 8 || hidden_dim < 8 || emb_dim < 8)
+    return AC_ERR_SHAPE;
+  if (model_dim % 8 != 0 || hidden_dim % 8 != 0 || emb_dim % 8 != 0 || emb_dim > 2048)
+    return AC_ERR_SHAPE;
+  if (h_dtype != AC_BF16 && h_dtype != AC_F32) return AC_ERR_DTYPE;
+  if (feat_dtype != AC_F16 && feat_dtype != AC_F32) return AC_ERR_DTYPE;
+  if (B == 0) return AC_OK;
+  if (!h || !W1 || !W2 || !feat || !workspace) return AC_ERR_NULL;
+  if (!aligned16(h) || !aligned16(W1) || !aligned16(b1) || !aligned16(W2) || !aligned16(b2) ||
+      !aligned16(feat) || !aligned16(workspace))
+    return AC_ERR_ALIGN;
+  if (workspace_bytes < ac::project_workspace_bytes(B, model_dim, hidden_dim, emb_dim))
+    return AC_ERR_WORKSPACE;
+  ac::ProjectLaunch p;
+  p.h = h; p.seq_len = seq_len; p.W1 = W1; p.b1 = b1; p.W2 = W2; p.b2 = b2;
+  p.feat = feat; p.ws = workspace;
+  p.B = B; p.S = S; p.dm = model_dim; p.hid = hidden_dim; p.E = emb_dim;
+  p.h_is_f32 = h_dtype == AC_F32; p.feat_is_f16 = feat_dtype == AC_F16;
+  p.normalize = normalize != 0;
+  hipError_t e = ac::launch_project(p, reinterpret_cast<hipStream_t>(stream));
+  return e == hipSuccess ? AC_OK : hip_fail(e);
+}
+
 }  // extern "C"

@@ -79,4 +79,16 @@ struct SearchLaunch {
 size_t search_workspace_bytes(int32_t N, int32_t E, int32_t B, int32_t k, int32_t is_f16);
 hipError_t launch_search(const SearchLaunch& p, hipStream_t stream);
 
+struct ProjectLaunch {
+  const void* h;            // device [B][S][dm], bf16 or fp32
+  const int32_t* seq_len;   // device [B] or nullptr
+  const float *W1, *b1;     // device [hid][dm], [hid] or nullptr
+  const float *W2, *b2;     // device [E][hid], [E] or nullptr
+  void* feat;               // device [B][E], fp16 or fp32
+  void* ws;
+  int32_t B, S, dm, hid, E, h_is_f32, feat_is_f16, normalize;
+};
+size_t project_workspace_bytes(int32_t B, int32_t dm, int32_t hid, int32_t E);
+hipError_t launch_project(const ProjectLaunch& p, hipStream_t stream);
+
 }  // namespace ac
