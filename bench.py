@@ -73,6 +73,10 @@ def main():
                     help="also time the per-layer mode (every layer runs its own search, reuse and "
                          "recompute launch; the whole chain is one HIP graph) and report it as "
                          "`per_layer_mode`")
+    ap.add_argument("--projector", action="store_true",
+                    help="also time the feature projector in front of the search (hidden states "
+                         "[B][S][Hq*D] bf16, hidden width a quarter of that, synthetic weights) and "
+                         "report it as `projector`; it is not part of the timed step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 1 GiB device copy (a kernel of known HBM traffic "
@@ -224,6 +228,46 @@ def main():
                      "launches_per_step": 4 * L if w.k == 1 else 5 * L}
         del Ql, Kl, Vl, Ol
 
+    # ------------------------- feature projector in front of the search (Algorithm 1), on request
+    projector = None
+    if args.projector and w.emb_dtype == "f16":
+        dm, hid, E = Hq * D, Hq * D // 4, w.emb_dim
+        gp = torch.Generator(device=dev).manual_seed(synth.seed_for(w, 9))
+        hs = [torch.randn(B, S, dm, generator=gp, device=dev).to(torch.bfloat16) for _ in range(4)]
+        W1 = torch.randn(hid, dm, generator=gp, device=dev) / dm ** 0.5
+        W2 = torch.randn(E, hid, generator=gp, device=dev) / hid ** 0.5
+        b1 = 0.1 * torch.randn(hid, generator=gp, device=dev)
+        b2 = 0.1 * torch.randn(E, generator=gp, device=dev)
+        pws = torch.empty(ac.attncache_project_workspace_bytes(B, dm, hid, E), dtype=torch.uint8,
+                          device=dev)
+        feat = torch.empty(B, E, dtype=torch.float16, device=dev)
+
+        def project_all():
+            for h in hs:
+                ac.attncache_project(h, W1, b1, W2, b2, feat, pws)
+
+        project_all()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph_p = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph_p, stream=side):
+                project_all()
+        torch.cuda.synchronize()
+        for _ in range(max(1, args.warmup)):
+            graph_p.replay()
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for _ in range(args.steps):
+            graph_p.replay()
+        torch.cuda.synchronize()
+        p_ms = (time.perf_counter() - t_start) * 1e3 / args.steps / len(hs)
+        projector = {"ms": p_ms, "model_dim": dm, "hidden_dim": hid, "emb_dim": E, "launches": 4,
+                     "dtype": "f32 (bf16 hidden states in)",
+                     "hidden_state_GBs": B * S * dm * 2 / (p_ms * 1e-3) / 1e9}
+        del hs, W1, W2, pws
+
     # ----------------------------------------- the denominator: exact attention on every query
     for _ in range(max(1, args.warmup // 2)):
         ac.attention_exact(Qf, Kf, Vf, Oef, causal=w.causal)
@@ -294,6 +338,8 @@ def main():
 
     if per_layer is not None:
         result["per_layer_mode"] = per_layer
+    if projector is not None:
+        result["projector"] = projector
 
     # ------------------------------------------- CPU oracle on a bounded sample (reported only)
     if not args.no_cpu_baseline:
