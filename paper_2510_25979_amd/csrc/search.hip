@@ -492,6 +492,7 @@ __global__ __launch_bounds__(kThreads) void finalize_topk_kernel(const SearchArg
 // ------------------------------------------------------------------- host side
 enum { kModeValu = 0, kModeMfma = 1, kModeMfmaBig = 2 };
 constexpr int kBigBatch = 64;   // above this many queries the query-stationary kernel is used
+constexpr int kBigRowsMin = 50000;   // and from this many database rows on, whatever the batch
 
 static void search_plan(int32_t N, int32_t mode, int32_t k, int32_t* rows_per_wg, int32_t* G) {
   int rpw;
@@ -522,10 +523,13 @@ static bool use_mfma(int32_t is_f16, int32_t metric, int32_t E) {
   return is_f16 && metric == 0 && E % 16 == 0 && E <= 512;
 }
 
-static int search_mode(int32_t is_f16, int32_t metric, int32_t E, int32_t B) {
+static int search_mode(int32_t is_f16, int32_t metric, int32_t E, int32_t B, int32_t N) {
   if (!use_mfma(is_f16, metric, E)) return kModeValu;
   const bool big_shape = E == 128 || E == 256 || E == 512;   // instantiated widths
-  return (B > kBigBatch && big_shape) ? kModeMfmaBig : kModeMfma;
+  // the query-stationary kernel streams a large database faster at any batch size (1M x 256:
+  // 94 us against 105-126 us for 4..64 queries); below kBigRowsMin rows both are latency-bound
+  // and the row-stationary kernel starts up faster
+  return (big_shape && (B > kBigBatch || N >= kBigRowsMin)) ? kModeMfmaBig : kModeMfma;
 }
 
 size_t search_workspace_bytes(int32_t N, int32_t E, int32_t B, int32_t k, int32_t is_f16) {
@@ -533,7 +537,7 @@ size_t search_workspace_bytes(int32_t N, int32_t E, int32_t B, int32_t k, int32_
   size_t need = 0;
   for (int metric = 0; metric < 2; ++metric) {
     int32_t rpw, G;
-    search_plan(N, search_mode(is_f16, metric, E, B), k, &rpw, &G);
+    search_plan(N, search_mode(is_f16, metric, E, B, N), k, &rpw, &G);
     size_t bytes = ((size_t)B * G * 8 + 255) / 256 * 256;
     if (k > 1) bytes += (size_t)B * k * rpw * 4;
     if (bytes > need) need = bytes;
@@ -577,7 +581,7 @@ hipError_t launch_search(const SearchLaunch& p, hipStream_t stream) {
   a.N = p.N; a.E = p.E; a.B = p.B; a.k = p.k; a.metric = p.metric;
   a.threshold = p.threshold;
   a.idx = p.idx; a.score = p.score; a.hit = p.hit;
-  const int mode = search_mode(p.is_f16, p.metric, p.E, p.B);
+  const int mode = search_mode(p.is_f16, p.metric, p.E, p.B, p.N);
   const bool mfma = mode == kModeMfma;
   search_plan(p.N, mode, p.k, &a.rows_per_wg, &a.G);
   unsigned char* ws = reinterpret_cast<unsigned char*>(p.ws);

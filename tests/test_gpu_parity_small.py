@@ -223,6 +223,9 @@ SEARCH_CASES = [
     (140000, 64, 40, 4, torch.float16, "ip", True),     # several row passes per workgroup
     (70001, 256, 130, 1, torch.float16, "ip", True),    # large batch: three chunks per workgroup, ragged end
     (66000, 512, 70, 2, torch.float16, "ip", True),     # large batch, widest rows, re-scored top-2
+    (50021, 256, 5, 1, torch.float16, "ip", True),      # large database, a handful of queries
+    (60000, 128, 33, 3, torch.float16, "ip", True),     # large database, one query past a block
+    (50000, 512, 1, 1, torch.float16, "ip", True),      # large database, a single query
 ]
 
 
