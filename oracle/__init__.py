@@ -36,7 +36,7 @@ def lib():
         L.oracle_apply.restype = i32
         L.oracle_apply.argtypes = [vp, vp, vp, vp] + [i32] * 9
         L.oracle_attention_exact.restype = i32
-        L.oracle_attention_exact.argtypes = [vp, vp, vp, vp, vp, vp] + [i32] * 6 + [f64]
+        L.oracle_attention_exact.argtypes = [vp, vp, vp, vp, vp, vp, vp] + [i32] * 6 + [f64]
         L.oracle_round_maps.restype = i32
         L.oracle_round_maps.argtypes = [vp, vp, i64, i32]
         L.oracle_project.restype = i32
@@ -102,8 +102,12 @@ def apply(maps, hit, V, layer_begin=0, out=None):
     return out
 
 
-def attention_exact(Q, K, V, causal=True, scale=0.0, row_sel=None, return_map=False, out=None):
-    """Recompute branch.  Q[B,Hq,S,D], K,V[B,Hkv,S,D] -> O[B,Hq,S,D] float64 (and P[B,Hq,S,S])."""
+def attention_exact(Q, K, V, causal=True, scale=0.0, row_sel=None, return_map=False, out=None,
+                    key_len=None):
+    """Recompute branch.  Q[B,Hq,S,D], K,V[B,Hkv,S,D] -> O[B,Hq,S,D] float64 (and P[B,Hq,S,S]).
+
+    key_len[B] (optional): real tokens per sentence of a right-padded batch; later keys are hidden.
+    """
     Q, K, V = _f32(Q), _f32(K), _f32(V)
     B, Hq, S, D = Q.shape
     Bk, Hkv, Sk, Dk = K.shape
@@ -113,7 +117,10 @@ def attention_exact(Q, K, V, causal=True, scale=0.0, row_sel=None, return_map=Fa
         out = np.zeros((B, Hq, S, D), np.float64)
     P = np.zeros((B, Hq, S, S), np.float64) if return_map else None
     rs = None if row_sel is None else _i32(row_sel)
-    _check(lib().oracle_attention_exact(_p(Q), _p(K), _p(V), _p(out), _p(P), _p(rs), B, Hq, Hkv,
+    kl = None if key_len is None else _i32(key_len)
+    if kl is not None and kl.shape != (B,):
+        raise ValueError("key_len must have one entry per batch item")
+    _check(lib().oracle_attention_exact(_p(Q), _p(K), _p(V), _p(out), _p(P), _p(rs), _p(kl), B, Hq, Hkv,
                                         S, D, int(bool(causal)), float(scale)),
            "oracle_attention_exact")
     return (out, P) if return_map else out

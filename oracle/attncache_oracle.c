@@ -191,7 +191,8 @@ int32_t oracle_apply(const float *maps, const int32_t *hit, const float *V,
 
 /*
  * Recompute branch: P = softmax(scale * Q K^T) row by row (keys j > i are
- * excluded when causal), O = P V.
+ * excluded when causal, keys at or beyond the sentence's length always),
+ * O = P V.
  *
  *   Q [B][Hq][S][D], K and V [B][Hkv][S][D], O [B][Hq][S][D] (fp64)
  *   P        NULL, or [B][Hq][S][S] fp64: the attention map itself, with
@@ -199,6 +200,11 @@ int32_t oracle_apply(const float *maps, const int32_t *hit, const float *V,
  *   row_sel  NULL, or [B]: batch items with row_sel[b] >= 0 are skipped
  *            (they were served by the reuse branch); their O / P are not
  *            written
+ *   key_len  NULL, or [B]: number of real tokens of sentence b in a batch
+ *            padded on the right to S (1 <= key_len[b] <= S).  Keys
+ *            j >= key_len[b] are padding and excluded for every row, the
+ *            attention mask of a padded batch.  Rows i >= key_len[b] are
+ *            padding themselves; they are computed by the same rule.
  *   scale    0 selects 1/sqrt(D)
  *
  * The row maximum is subtracted before exponentiation; this leaves the
@@ -206,11 +212,14 @@ int32_t oracle_apply(const float *maps, const int32_t *hit, const float *V,
  */
 int32_t oracle_attention_exact(const float *Q, const float *K, const float *V,
                                double *O, double *P, const int32_t *row_sel,
-                               int32_t B, int32_t Hq, int32_t Hkv, int32_t S,
-                               int32_t D, int32_t causal, double scale) {
+                               const int32_t *key_len, int32_t B, int32_t Hq,
+                               int32_t Hkv, int32_t S, int32_t D,
+                               int32_t causal, double scale) {
   if (!Q || !K || !V || !O) return ORACLE_ERR_ARG;
   if (B < 0 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || S < 1 || D < 1)
     return ORACLE_ERR_ARG;
+  for (int32_t b = 0; key_len && b < B; ++b)
+    if (key_len[b] < 1 || key_len[b] > S) return ORACLE_ERR_INDEX;
   if (scale == 0.0) scale = 1.0 / sqrt((double)D);
   const int32_t g = Hq / Hkv;
   const int64_t tiles = (int64_t)B * Hq;
@@ -233,7 +242,9 @@ int32_t oracle_attention_exact(const float *Q, const float *K, const float *V,
       continue;
     }
     for (int32_t i = 0; i < S; ++i) {
+      const int32_t len = key_len ? key_len[b] : S;
       int32_t nj = causal ? i + 1 : S;
+      if (nj > len) nj = len;
       double m = -INFINITY;
       for (int32_t j = 0; j < nj; ++j) {
         double acc = 0.0;

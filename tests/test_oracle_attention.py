@@ -116,6 +116,45 @@ def test_row_sel_skips_served_items(oracle_mod):
     assert (out[1] == 7.0).all()
 
 
+@pytest.mark.parametrize("causal", [True, False])
+def test_key_lengths_against_library_mask(oracle_mod, causal):
+    # a right-padded batch: keys at or beyond the sentence's length are hidden from every row
+    B, H, S, D = 3, 2, 19, 8
+    Q, K, V = _rand((B, H, S, D), 31), _rand((B, H, S, D), 32), _rand((B, H, S, D), 33)
+    lens = np.array([19, 7, 1], np.int32)
+    O, P = oracle_mod.attention_exact(Q, K, V, causal=causal, key_len=lens, return_map=True)
+    q, k, v = (torch.from_numpy(x).double() for x in (Q, K, V))
+    keep = torch.arange(S)[None, :] < torch.from_numpy(lens)[:, None]          # [B, S] keys
+    mask = keep[:, None, None, :].expand(B, 1, S, S).clone()
+    if causal:
+        mask &= torch.ones(S, S, dtype=torch.bool).tril()
+    ref = F.scaled_dot_product_attention(q, k, v, attn_mask=mask)
+    np.testing.assert_allclose(O, ref.numpy(), rtol=1e-11, atol=1e-12)
+    for b in range(B):
+        assert (P[b, :, :, lens[b]:] == 0.0).all()                            # exact zeros on padding
+        np.testing.assert_allclose(P[b].sum(-1), 1.0, rtol=1e-13)
+    # what lies in the padding does not matter
+    K2, V2 = K.copy(), V.copy()
+    for b in range(B):
+        K2[b, :, lens[b]:], V2[b, :, lens[b]:] = 1e3, -1e3
+    O2 = oracle_mod.attention_exact(Q, K2, V2, causal=causal, key_len=lens)
+    assert np.array_equal(O2, O)
+    # a sentence of one token: every row returns V[0]
+    np.testing.assert_allclose(O[2], np.broadcast_to(V[2, :, :1].astype(np.float64), O[2].shape),
+                               rtol=1e-15)
+    # the full length is the unpadded result
+    full = oracle_mod.attention_exact(Q, K, V, causal=causal)
+    assert np.array_equal(O[0], full[0])
+    # causal rows inside the sentence never saw the padding anyway
+    if causal:
+        for b in range(B):
+            assert np.array_equal(O[b, :, :lens[b]], full[b, :, :lens[b]])
+    with pytest.raises(RuntimeError):
+        oracle_mod.attention_exact(Q, K, V, key_len=np.array([19, 0, 1], np.int32))
+    with pytest.raises(RuntimeError):
+        oracle_mod.attention_exact(Q, K, V, key_len=np.array([20, 1, 1], np.int32))
+
+
 # -------------------------------------------------------------------- map reuse
 
 def test_identity_map_returns_v_exactly(oracle_mod):
