@@ -234,12 +234,21 @@ int32_t attncache_apply(const attncache_db *db, const int32_t *hit,
  *   row_sel   NULL, or DEVICE [B] int32: items with row_sel[b] >= 0 are
  *             skipped and their O rows not written -- pass the hit array of
  *             attncache_search to compute only the misses.
+ *   key_len   NULL, or DEVICE [B] int32: number of real tokens of sentence b
+ *             in a batch padded on the right to S (values are clamped to
+ *             [1, S]).  Keys j >= key_len[b] are hidden from every row (the
+ *             attention mask of a padded batch, needed for non-causal
+ *             models; with causal != 0 the rows inside the sentence never see
+ *             the padding anyway) and chunks of keys that lie wholly in the
+ *             padding are not read.  Rows i >= key_len[b] are padding
+ *             themselves; they are computed by the same rule.
  *   scale     0 selects 1/sqrt(D).
  *
  * Softmax statistics and accumulators are fp32.
  */
 int32_t attention_exact(const void *Q, const void *K, const void *V, void *O,
-                        const int32_t *row_sel, int32_t B, int32_t Hq,
+                        const int32_t *row_sel, const int32_t *key_len,
+                        int32_t B, int32_t Hq,
                         int32_t Hkv, int32_t S, int32_t D, int32_t dtype,
                         int32_t causal, float scale, void *stream);
 

@@ -79,7 +79,7 @@ def lib():
         L.attncache_apply.restype = i32
         L.attncache_apply.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
         L.attention_exact.restype = i32
-        L.attention_exact.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, f32, vp]
+        L.attention_exact.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, f32, vp]
         L.attncache_insert.restype = i32
         L.attncache_insert.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp]
         L.attncache_cache_stats.restype = i32
@@ -297,8 +297,9 @@ def attncache_insert(db: Database, Q: torch.Tensor, K: torch.Tensor, V: torch.Te
 def attention_exact(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, O: torch.Tensor, *,
                     causal: bool = True, scale: float = 0.0,
                     row_sel: Optional[torch.Tensor] = None,
+                    key_len: Optional[torch.Tensor] = None,
                     stream: Optional[torch.cuda.Stream] = None) -> None:
-    """Q,O [B,Hq,S,D]; K,V [B,Hkv,S,D]; bf16 or f32."""
+    """Q,O [B,Hq,S,D]; K,V [B,Hkv,S,D]; bf16 or f32; row_sel, key_len [B] int32."""
     if Q.dim() != 4 or K.dim() != 4:
         raise ValueError("Q must be [B,Hq,S,D] and K,V [B,Hkv,S,D]")
     B, Hq, S, D = Q.shape
@@ -310,7 +311,8 @@ def attention_exact(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, O: torch.
     vp = _dev(V, "V", Q.dtype, (B, Hkv, S, D))
     op = _dev(O, "O", Q.dtype, (B, Hq, S, D))
     rp = None if row_sel is None else _dev(row_sel, "row_sel", torch.int32, (B,))
-    _check(lib().attention_exact(qp, kp, vp, op, rp, B, Hq, Hkv, S, D, _DTYPE_CODE[Q.dtype],
+    lp = None if key_len is None else _dev(key_len, "key_len", torch.int32, (B,))
+    _check(lib().attention_exact(qp, kp, vp, op, rp, lp, B, Hq, Hkv, S, D, _DTYPE_CODE[Q.dtype],
                                  int(causal), float(scale), _stream(stream)), "attention_exact")
 
 

@@ -348,8 +348,9 @@ int32_t attncache_cache_reset(attncache_db* db) {
 }
 
 int32_t attention_exact(const void* Q, const void* K, const void* V, void* O,
-                        const int32_t* row_sel, int32_t B, int32_t Hq, int32_t Hkv, int32_t S,
-                        int32_t D, int32_t dtype, int32_t causal, float scale, void* stream) {
+                        const int32_t* row_sel, const int32_t* key_len, int32_t B, int32_t Hq,
+                        int32_t Hkv, int32_t S, int32_t D, int32_t dtype, int32_t causal,
+                        float scale, void* stream) {
   if (B < 0 || Hq < 1 || Hkv < 1 || S < 1 || D < 1 || Hq % Hkv != 0) return AC_ERR_SHAPE;
   if (dtype == AC_BF16) {
     if (S % 32 != 0 || (D != 64 && D != 128)) return AC_ERR_SHAPE;
@@ -363,7 +364,7 @@ int32_t attention_exact(const void* Q, const void* K, const void* V, void* O,
   if (!Q || !K || !V || !O) return AC_ERR_NULL;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return AC_ERR_ALIGN;
   ac::ExactLaunch p;
-  p.Q = Q; p.K = K; p.V = V; p.O = O; p.row_sel = row_sel;
+  p.Q = Q; p.K = K; p.V = V; p.O = O; p.row_sel = row_sel; p.key_len = key_len;
   p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.S = S; p.D = D;
   p.causal = causal != 0; p.is_f32 = dtype == AC_F32; p.scale = scale;
   hipError_t e = ac::launch_exact(p, reinterpret_cast<hipStream_t>(stream));

@@ -34,6 +34,7 @@ struct ExactArgs {
   const void *Q, *K, *V;
   void* O;
   const int32_t* row_sel;
+  const int32_t* key_len;   // real tokens per batch item of a right-padded batch, or nullptr
   int32_t B, Hq, Hkv, S;
   int32_t heads_per_wg;
   int32_t n_rblk;
@@ -108,6 +109,7 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
 
   // per tile (the helpers below read these by reference)
   int u = 0, h = 0, R = 0, b = 0, r0 = 0, n_chunk = 0;
+  int Sk = S;   // keys this tile's queries may see at all: the sentence's length in a padded batch
   bool active = false;
   const bf16_t* Ksrc = nullptr;
   const bf16_t* Vsrc = nullptr;
@@ -214,9 +216,9 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
                     __builtin_bit_cast(bf16x8, q[ks]), s);
     return s;
   };
-  // hide the keys this query row must not see (beyond the diagonal or the end of the sequence)
+  // hide the keys this query row must not see (beyond the diagonal or the end of the sentence)
   auto hide = [&](f32x16& s, int c, int jb) {
-    const int limit = (CAUSAL ? min(r0 + il, S - 1) : S - 1) - c * kLChunk - 32 * jb - 4 * kh;
+    const int limit = (CAUSAL ? min(r0 + il, Sk - 1) : Sk - 1) - c * kLChunk - 32 * jb - 4 * kh;
 #pragma unroll
     for (int v = 0; v < 16; ++v)
       if (8 * (v >> 2) + (v & 3) > limit) s[v] = -INFINITY;
@@ -318,8 +320,8 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
   // chunk c through the masked variant (exact for every chunk, only slower)
   auto tail_step = [&](const bf16_t* kb, const bf16_t* vb, int c) {
     if (!active) return;
-    const int nj = min(kLChunk, S - c * kLChunk);
-    int nblk = nj >> 5;
+    const int nj = min(kLChunk, Sk - c * kLChunk);
+    int nblk = (nj + 31) >> 5;
     if (CAUSAL) nblk = min(nblk, (r0 >> 5) + 1 - 2 * c);
     if (nblk > 0) step(kb, vb, c, nblk, true);
   };
@@ -389,7 +391,8 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
     Vsrc = reinterpret_cast<const bf16_t*>(a.V) + (size_t)u * S * D;
     kptr = Ksrc + crow * D + 8 * kpiece;
     vptr = Vsrc + crow * D + 8 * vpiece;
-    const int last_key = CAUSAL ? min(S, kChunk * (R + 1)) : S;
+    Sk = a.key_len ? min(max(a.key_len[b], 1), S) : S;
+    const int last_key = CAUSAL ? min(Sk, kChunk * (R + 1)) : Sk;
     n_chunk = (last_key + kLChunk - 1) / kLChunk;
 
     if (RESIDENT) {
@@ -422,7 +425,7 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
       // main loop runs only the test-free variant, two chunks per trip so that stages
       // alternate without pointer arithmetic.  The few chunks from c_split on go through the
       // masked variant.
-      const int c_split = CAUSAL ? min(2 * R, S / kLChunk) : S / kLChunk;
+      const int c_split = CAUSAL ? min(2 * R, Sk / kLChunk) : Sk / kLChunk;
       prefetch(kb0, vb0, 0);
       int c = 0;
       for (; c + 1 < c_split; c += 2) {
@@ -468,7 +471,8 @@ __global__ __launch_bounds__(kWave) void exact_f32_kernel(const ExactArgs a, int
   const float* K = reinterpret_cast<const float*>(a.K) + ((size_t)b * a.Hkv + h / g) * (size_t)S * D;
   const float* V = reinterpret_cast<const float*>(a.V) + ((size_t)b * a.Hkv + h / g) * (size_t)S * D;
   float* o = reinterpret_cast<float*>(a.O) + (((size_t)b * a.Hq + h) * S + i) * (size_t)D;
-  const int nj = causal ? i + 1 : S;
+  const int len = a.key_len ? min(max(a.key_len[b], 1), S) : S;   // keys beyond it are padding
+  const int nj = min(causal ? i + 1 : S, len);
   float mx = -INFINITY;
   for (int j = lane; j < nj; j += kWave) {
     float acc = 0.f;
@@ -513,7 +517,7 @@ static hipError_t launch_exact_bf16(const ExactArgs& a, dim3 grid, hipStream_t s
 hipError_t launch_exact(const ExactLaunch& p, hipStream_t stream) {
   if (p.B == 0) return hipSuccess;
   ExactArgs a;
-  a.Q = p.Q; a.K = p.K; a.V = p.V; a.O = p.O; a.row_sel = p.row_sel;
+  a.Q = p.Q; a.K = p.K; a.V = p.V; a.O = p.O; a.row_sel = p.row_sel; a.key_len = p.key_len;
   a.B = p.B; a.Hq = p.Hq; a.Hkv = p.Hkv; a.S = p.S;
   a.n_rblk = (p.S + kChunk - 1) / kChunk;
   a.n_kvtiles = p.B * p.Hkv;

@@ -46,6 +46,7 @@ struct ExactLaunch {
   const void *Q, *K, *V;
   void* O;
   const int32_t* row_sel;
+  const int32_t* key_len;   // device [B] or nullptr
   int32_t B, Hq, Hkv, S, D, causal, is_f32;
   float scale;
 };

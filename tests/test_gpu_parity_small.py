@@ -150,6 +150,56 @@ def test_exact_matches_oracle(ac, oracle_mod, case):
         assert (O[1] == 7.0).all()
 
 
+PADDED_CASES = [
+    # B, Hq, Hkv, S, D, causal, dtype, lengths
+    (6, 2, 2, 128, 64, False, torch.bfloat16, [128, 1, 33, 64, 65, 100]),      # encoder-style, resident
+    (5, 4, 1, 128, 128, False, torch.bfloat16, [127, 96, 32, 31, 2]),          # four heads share K, V
+    (4, 2, 2, 128, 64, True, torch.bfloat16, [128, 70, 5, 64]),                # causal: only the padding rows change
+    (3, 2, 2, 96, 128, False, torch.bfloat16, [96, 40, 65]),
+    (5, 2, 1, 640, 64, False, torch.bfloat16, [640, 1, 64, 333, 577]),         # streaming: chunks in the padding are skipped
+    (4, 2, 2, 416, 128, True, torch.bfloat16, [416, 129, 200, 31]),            # streaming, causal, ragged S
+    (1, 1, 1, 1024, 128, False, torch.bfloat16, [700]),
+    (4, 3, 1, 45, 24, False, torch.float32, [45, 1, 17, 44]),                  # vector-ALU path
+    (3, 2, 2, 32, 64, True, torch.float32, [32, 9, 1]),
+]
+
+
+@pytest.mark.parametrize("case", PADDED_CASES, ids=lambda c: "B%d-H%d/%d-S%d-D%d-%s-%s" % (
+    c[0], c[1], c[2], c[3], c[4], "causal" if c[5] else "dense", str(c[6]).split(".")[-1]))
+def test_exact_with_sentence_lengths_matches_oracle(ac, oracle_mod, case):
+    # a right-padded batch: keys at or beyond the sentence's length are hidden from every row;
+    # the padding holds large values that would show in the result if they were read into it
+    B, Hq, Hkv, S, D, causal, dt, lens = case
+    g = _gen(900 + S + D)
+    Q = torch.randn(B, Hq, S, D, generator=g).to(dt)
+    K = torch.randn(B, Hkv, S, D, generator=g).to(dt)
+    V = torch.randn(B, Hkv, S, D, generator=g).to(dt)
+    key_len = torch.tensor(lens, dtype=torch.int32)
+    Kc, Vc = K.clone(), V.clone()                    # ordinary values everywhere, for the last part
+    for b in range(B):
+        K[b, :, lens[b]:] = 3.0
+        V[b, :, lens[b]:] = 50.0
+    O = torch.full((B, Hq, S, D), 7.0, dtype=dt, device="cuda")
+    ac.attention_exact(Q.cuda(), K.cuda(), V.cuda(), O, causal=causal, key_len=key_len.cuda())
+    torch.cuda.synchronize()
+    ref = oracle_mod.attention_exact(parity.to_np(Q), parity.to_np(K), parity.to_np(V), causal=causal,
+                                     key_len=key_len.numpy())
+    err = parity.max_abs_err(O, ref)
+    assert err <= parity.TOL[dt], err
+    # lengths outside [1, S] are clamped, and the full length equals the call without lengths
+    wild = torch.tensor([S + 9 if b % 2 else 0 for b in range(B)], dtype=torch.int32)
+    O2 = torch.empty_like(O)
+    ac.attention_exact(Q.cuda(), Kc.cuda(), Vc.cuda(), O2, causal=causal, key_len=wild.cuda())
+    torch.cuda.synchronize()
+    ref2 = oracle_mod.attention_exact(parity.to_np(Q), parity.to_np(Kc), parity.to_np(Vc), causal=causal,
+                                      key_len=wild.clamp(1, S).numpy())
+    assert parity.max_abs_err(O2, ref2) <= parity.TOL[dt]
+    O3 = torch.empty_like(O)
+    ac.attention_exact(Q.cuda(), Kc.cuda(), Vc.cuda(), O3, causal=causal)
+    torch.cuda.synchronize()
+    assert torch.equal(O3[1::2], O2[1::2])
+
+
 def test_exact_many_tiles_per_workgroup_with_routing(ac, oracle_mod):
     # enough (batch, head) tiles that one workgroup walks several of them back to back, with
     # some batch items routed away (their tiles are skipped in the middle of a walk)
