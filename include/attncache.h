@@ -283,6 +283,10 @@ int32_t attention_exact(const void *Q, const void *K, const void *V, void *O,
  *             at all.  Slots of one call must be distinct (equal slots race).
  *   row_sel   NULL or DEVICE [B] int32: items with row_sel[b] >= 0 are skipped
  *             entirely (pass the hit array to handle only the misses).
+ *   key_len   NULL or DEVICE [B] int32: real tokens of sentence b in a batch
+ *             padded on the right to S, as for attention_exact (clamped to
+ *             [1, S]); keys in the padding get weight zero, and those zeros
+ *             are what the stored map holds in their columns.
  *   Q         DEVICE [B][layer_count][Hq][S][D] bf16; K, V DEVICE
  *             [B][layer_count][Hkv][S][D]; O DEVICE like Q.
  *   scale     0 selects 1/sqrt(D).
@@ -292,7 +296,8 @@ int32_t attention_exact(const void *Q, const void *K, const void *V, void *O,
  */
 int32_t attncache_insert(attncache_db *db, const void *feat,
                          const int32_t *slot, const int32_t *row_sel,
-                         const void *Q, const void *K, const void *V, void *O,
+                         const int32_t *key_len, const void *Q, const void *K,
+                         const void *V, void *O,
                          int32_t B, int32_t layer_begin, int32_t layer_count,
                          float scale, void *stream);
 

@@ -81,7 +81,7 @@ def lib():
         L.attention_exact.restype = i32
         L.attention_exact.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, f32, vp]
         L.attncache_insert.restype = i32
-        L.attncache_insert.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp]
+        L.attncache_insert.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, f32, vp]
         L.attncache_cache_stats.restype = i32
         L.attncache_cache_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
         L.attncache_cache_reset.restype = i32
@@ -274,9 +274,10 @@ def attncache_cache_reset(db: Database) -> None:
 
 def attncache_insert(db: Database, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, O: torch.Tensor, *,
                      slot: Optional[torch.Tensor] = None, feat: Optional[torch.Tensor] = None,
-                     row_sel: Optional[torch.Tensor] = None, layer_begin: int = 0,
+                     row_sel: Optional[torch.Tensor] = None,
+                     key_len: Optional[torch.Tensor] = None, layer_begin: int = 0,
                      scale: float = 0.0, stream: Optional[torch.cuda.Stream] = None) -> None:
-    """Q,O [B,Lc,Hq,S,D]; K,V [B,Lc,Hkv,S,D] bf16; slot, row_sel [B] int32; feat [B,E]."""
+    """Q,O [B,Lc,Hq,S,D]; K,V [B,Lc,Hkv,S,D] bf16; slot, row_sel, key_len [B] int32; feat [B,E]."""
     d = db.desc
     if Q.dim() != 5:
         raise ValueError("Q must be [B,Lc,Hq,S,D]")
@@ -288,9 +289,10 @@ def attncache_insert(db: Database, Q: torch.Tensor, K: torch.Tensor, V: torch.Te
     op = _dev(O, "O", dt, (B, Lc, d.n_q_heads, d.seq_len, d.head_dim))
     sp = None if slot is None else _dev(slot, "slot", torch.int32, (B,))
     rp = None if row_sel is None else _dev(row_sel, "row_sel", torch.int32, (B,))
+    lp = None if key_len is None else _dev(key_len, "key_len", torch.int32, (B,))
     fdt = torch.float16 if d.emb_dtype == AC_F16 else torch.float32
     fp = None if feat is None else _dev(feat, "feat", fdt, (B, d.emb_dim))
-    _check(lib().attncache_insert(db.handle, fp, sp, rp, qp, kp, vp, op, B, layer_begin, Lc,
+    _check(lib().attncache_insert(db.handle, fp, sp, rp, lp, qp, kp, vp, op, B, layer_begin, Lc,
                                   float(scale), _stream(stream)), "attncache_insert")
 
 

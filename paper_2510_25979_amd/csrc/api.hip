@@ -372,9 +372,9 @@ int32_t attention_exact(const void* Q, const void* K, const void* V, void* O,
 }
 
 int32_t attncache_insert(attncache_db* db, const void* feat, const int32_t* slot,
-                         const int32_t* row_sel, const void* Q, const void* K, const void* V,
-                         void* O, int32_t B, int32_t layer_begin, int32_t layer_count, float scale,
-                         void* stream) {
+                         const int32_t* row_sel, const int32_t* key_len, const void* Q,
+                         const void* K, const void* V, void* O, int32_t B, int32_t layer_begin,
+                         int32_t layer_count, float scale, void* stream) {
   if (!db) return AC_ERR_NULL;
   const attncache_db_desc& d = db->d;
   if (B < 0 || layer_begin < 0 || layer_count < 0 || layer_begin + layer_count > d.n_layers)
@@ -395,7 +395,7 @@ int32_t attncache_insert(attncache_db* db, const void* feat, const int32_t* slot
   p.Q = Q; p.K = K; p.V = V; p.O = O;
   p.maps = const_cast<void*>(db->maps);   // the one entry point that writes the borrowed stores
   p.feat = feat; p.emb = const_cast<void*>(db->emb);
-  p.slot = slot; p.row_sel = row_sel;
+  p.slot = slot; p.row_sel = row_sel; p.key_len = key_len;
   p.B = B; p.M = d.n_entries; p.L = d.n_layers; p.layer_begin = layer_begin; p.Lc = layer_count;
   p.Hq = d.n_q_heads; p.Hkv = d.n_kv_heads; p.S = d.seq_len; p.D = d.head_dim;
   p.causal = d.causal != 0; p.packed = d.map_layout == AC_LAYOUT_PACKED;

@@ -30,7 +30,7 @@ constexpr int kKPadI = 8;   // elements of padding per staged K row
 struct InsertArgs {
   const void *Q, *K, *V;
   void *O, *maps;
-  const int32_t *slot, *row_sel;
+  const int32_t *slot, *row_sel, *key_len;
   int32_t B, M, L, layer_begin, Lc, Hq, Hkv, S;
   int32_t n_rblk, n_tiles;
   float scale_log2e;
@@ -60,6 +60,8 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_kernel(const InsertAr
   const int l = (tile / a.Hq) % a.Lc;
   const int b = tile / (a.Hq * a.Lc);
   if (a.row_sel && a.row_sel[b] >= 0) return;
+  // real tokens of this sentence in a right-padded batch: later keys get weight zero
+  const int len = a.key_len ? min(max(a.key_len[b], 1), S) : S;
   const int entry = a.slot ? a.slot[b] : -1;
   const bool keep = entry >= 0 && entry < a.M;   // anything else: compute O only
 
@@ -103,7 +105,8 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_kernel(const InsertAr
     if (CAUSAL) nblk = min(nblk, (r0 - j0) / 32 + 1);
     return max(nblk, 0);
   };
-  // scores^T of key block jb of the staged chunk (keys beyond the diagonal hidden)
+  // scores^T of key block jb of the staged chunk (keys beyond the diagonal or in the padding
+  // hidden; block 0 always has a visible key, so the running maximum is finite from then on)
   auto scores = [&](int c, int jb) {
     f32x16 s;
 #pragma unroll
@@ -112,10 +115,13 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_kernel(const InsertAr
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks)
       s = mfma_bf16(*reinterpret_cast<const bf16x8*>(krow + 16 * ks), __builtin_bit_cast(bf16x8, q[ks]), s);
-    if (CAUSAL && c * kChunk + 32 * jb == r0) {
+    const int j00 = c * kChunk + 32 * jb;
+    if ((CAUSAL && j00 == r0) || j00 + 32 > len) {   // wave-uniform: most blocks skip the tests
+      int limit = len - 1 - j00;
+      if (CAUSAL) limit = min(limit, r0 + il - j00);
 #pragma unroll
       for (int v = 0; v < 16; ++v)
-        if (mfma_row(v, kh) > il) s[v] = -INFINITY;
+        if (mfma_row(v, kh) > limit) s[v] = -INFINITY;
     }
     return s;
   };
@@ -261,7 +267,7 @@ hipError_t launch_insert(const InsertLaunch& p, hipStream_t stream) {
   }
   InsertArgs a;
   a.Q = p.Q; a.K = p.K; a.V = p.V; a.O = p.O; a.maps = p.maps;
-  a.slot = p.slot; a.row_sel = p.row_sel;
+  a.slot = p.slot; a.row_sel = p.row_sel; a.key_len = p.key_len;
   a.B = p.B; a.M = p.M; a.L = p.L; a.layer_begin = p.layer_begin; a.Lc = p.Lc;
   a.Hq = p.Hq; a.Hkv = p.Hkv; a.S = p.S;
   a.n_rblk = (p.S + kChunk - 1) / kChunk;

@@ -60,6 +60,7 @@ struct InsertLaunch {
   void* emb;               // device: the whole feature store
   const int32_t* slot;     // device [B] or nullptr (compute O only)
   const int32_t* row_sel;  // device [B] or nullptr
+  const int32_t* key_len;  // device [B] or nullptr
   int32_t B, M, L, layer_begin, Lc, Hq, Hkv, S, D, causal, packed;
   int32_t emb_row_bytes;
   float scale;

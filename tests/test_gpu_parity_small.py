@@ -501,10 +501,11 @@ INSERT_CASES = [
 ]
 
 
+@pytest.mark.parametrize("padded", [False, True], ids=["full", "padded"])
 @pytest.mark.parametrize("layout", ["dense", "packed"])
 @pytest.mark.parametrize("case", INSERT_CASES, ids=lambda c: "B%d-L%d-H%d/%d-S%d-D%d-%s" % (
     c[0], c[1], c[2], c[3], c[4], c[5], "causal" if c[6] else "dense"))
-def test_insert_stores_the_oracles_map_and_output(ac, oracle_mod, case, layout):
+def test_insert_stores_the_oracles_map_and_output(ac, oracle_mod, case, layout, padded):
     B, L, Hq, Hkv, S, D, causal = case
     M, E = 6, 32
     g = _gen(900 + S + D)
@@ -512,6 +513,12 @@ def test_insert_stores_the_oracles_map_and_output(ac, oracle_mod, case, layout):
     K = torch.randn(B, L, Hkv, S, D, generator=g).to(torch.bfloat16)
     V = torch.randn(B, L, Hkv, S, D, generator=g).to(torch.bfloat16)
     feat = torch.randn(B, E, generator=g).half()
+    key_len = None
+    if padded:       # a right-padded batch: the stored map must hold exact zeros in the padding
+        key_len = torch.tensor([S - 27, 33, S][:B], dtype=torch.int32)
+        for b in range(B):
+            K[b, :, :, key_len[b]:] = 3.0
+            V[b, :, :, key_len[b]:] = 50.0
     tile = ac.packed_tile_elems(S, causal) if layout == "packed" else S * S
     sentinel = 0.5
     maps = torch.full((M, L, Hq, tile), sentinel, dtype=torch.bfloat16, device="cuda")
@@ -520,13 +527,15 @@ def test_insert_stores_the_oracles_map_and_output(ac, oracle_mod, case, layout):
                                n_kv_heads=Hkv, head_dim=D, causal=causal, seq_len=S)
     slot = torch.tensor(([4, -1, 1] if B == 3 else [3, 0]), dtype=torch.int32)
     O = torch.full((B, L, Hq, S, D), 7.0, dtype=torch.bfloat16, device="cuda")
-    ac.attncache_insert(db, Q.cuda(), K.cuda(), V.cuda(), O, slot=slot.cuda(), feat=feat.cuda())
+    ac.attncache_insert(db, Q.cuda(), K.cuda(), V.cuda(), O, slot=slot.cuda(), feat=feat.cuda(),
+                        key_len=None if key_len is None else key_len.cuda())
     torch.cuda.synchronize()
 
     maps_h = parity.to_np(maps)
     for l in range(L):
         ref_O, P = oracle_mod.attention_exact(parity.to_np(Q[:, l]), parity.to_np(K[:, l]),
-                                              parity.to_np(V[:, l]), causal=causal, return_map=True)
+                                              parity.to_np(V[:, l]), causal=causal, return_map=True,
+                                              key_len=None if key_len is None else key_len.numpy())
         assert parity.max_abs_err(O[:, l].contiguous(), ref_O) <= 2e-2
         P_r = oracle_mod.round_maps(P, oracle_mod.ROUND_BF16)
         for b in range(B):
