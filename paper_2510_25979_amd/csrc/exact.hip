@@ -91,17 +91,6 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
   const int il = lane & 31, kh = lane >> 5;
   const int S = a.S, g = a.Hq / a.Hkv;
-  if (RESIDENT && a.row_sel) {
-    // routed launch: leave at once when none of this workgroup's tiles has anything to do (a
-    // batch that was served entirely by the reuse branch then costs a few scalar loads)
-    bool any = false;
-    const int per_u = (g / a.heads_per_wg) * a.n_rblk;
-    for (int t = blockIdx.x; t < a.n_blocks && !any; t += gridDim.x) {
-      const int ut = ((t >> 3) / per_u) * 8 + (t & 7);
-      any = ut < a.n_kvtiles && a.row_sel[ut / a.Hkv] < 0;
-    }
-    if (!any) return;
-  }
   // Sequences of up to 128 keys are RESIDENT: both 64-key chunks of K and V sit in the two
   // stages for the whole tile, the workgroup walks all heads_per_wg query heads that share
   // them, and between the one barrier after the copy and the end of the tile the four waves
@@ -370,36 +359,40 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
       }
   };
 
-  // One tile per workgroup, or (when queries are routed, so that many tiles may have nothing
-  // to do) a fixed number of workgroups that each take every gridDim.x-th tile: skipping a
-  // tile then costs a scalar test instead of a workgroup launch.
-  bool first_tile = true;
-  int bid = blockIdx.x;
-  do {   // a loop in the resident variant only (the condition below is constant otherwise)
-    const int slot = bid >> 3;
+  if constexpr (RESIDENT) {
+    // A fixed number of workgroups, each taking every gridDim.x-th tile: skipping a tile whose
+    // batch item was served by the reuse branch costs a scalar test instead of a workgroup
+    // launch, and the copies of the next tile's K and V are started before the last head of
+    // the current tile is written out, so stores and loads of one workgroup overlap.
     const int hslots = g / a.heads_per_wg;
-    const int per_u = hslots * a.n_rblk;
-    u = (slot / per_u) * 8 + (bid & 7);   // ids equal mod 8 (one XCD) share K, V in its L2
-    if (u >= a.n_kvtiles) continue;
-    const int h_first = (u % a.Hkv) * g + ((slot % per_u) / a.n_rblk) * a.heads_per_wg;
-    R = a.n_rblk - 1 - (slot % per_u) % a.n_rblk;   // heaviest row blocks first
-    b = u / a.Hkv;
-    if (a.row_sel && a.row_sel[b] >= 0) continue;
-    if (!first_tile) __syncthreads();   // the previous tile may still be read or staged in LDS
-    first_tile = false;
-    Ksrc = reinterpret_cast<const bf16_t*>(a.K) + (size_t)u * S * D;
-    Vsrc = reinterpret_cast<const bf16_t*>(a.V) + (size_t)u * S * D;
-    kptr = Ksrc + crow * D + 8 * kpiece;
-    vptr = Vsrc + crow * D + 8 * vpiece;
-    Sk = a.key_len ? min(max(a.key_len[b], 1), S) : S;
-    const int last_key = CAUSAL ? min(Sk, kChunk * (R + 1)) : Sk;
-    n_chunk = (last_key + kLChunk - 1) / kLChunk;
-
-    if (RESIDENT) {
+    auto locate = [&](int from) {   // first tile at or after `from` (same stride) that has work
+      for (int t = from; t < a.n_blocks; t += gridDim.x) {
+        const int ut = ((t >> 3) / hslots) * 8 + (t & 7);   // ids equal mod 8 (one XCD) share K, V
+        if (ut < a.n_kvtiles && !(a.row_sel && a.row_sel[ut / a.Hkv] >= 0)) return t;
+      }
+      return -1;
+    };
+    int h_first = 0;
+    auto enter = [&](int t) {       // tile variables, and its K and V on their way
+      const int slot = t >> 3;
+      u = (slot / hslots) * 8 + (t & 7);
+      h_first = (u % a.Hkv) * g + (slot % hslots) * a.heads_per_wg;
+      b = u / a.Hkv;
+      Ksrc = reinterpret_cast<const bf16_t*>(a.K) + (size_t)u * S * D;
+      Vsrc = reinterpret_cast<const bf16_t*>(a.V) + (size_t)u * S * D;
+      kptr = Ksrc + crow * D + 8 * kpiece;
+      vptr = Vsrc + crow * D + 8 * vpiece;
+      Sk = a.key_len ? min(max(a.key_len[b], 1), S) : S;
+      n_chunk = (Sk + kLChunk - 1) / kLChunk;
       prefetch(kb0, vb0, 0);
       if (n_chunk > 1) prefetch(kb1, vb1, 1);
+    };
+    int t = locate(blockIdx.x);
+    if (t < 0) return;   // e.g. a batch served entirely by the reuse branch: a few scalar loads
+    enter(t);
+    while (true) {
       publish();
-      const int rot = slot & 3;
+      const int rot = (t >> 3) & 3;
       for (int hl = 0; hl < a.heads_per_wg; ++hl) {
         h = h_first + hl;
         // causal work grows with the row block and wave i always runs on SIMD i: rotating the
@@ -408,43 +401,67 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
         active = r0 < S;
         begin_head();
         for (int c = 0; c < n_chunk; ++c) tail_step(c ? kb1 : kb0, c ? vb1 : vb0, c);
-        if (a.heads_per_wg == 1) break;   // stored below, through the (now dead) stages
+        if (hl + 1 == a.heads_per_wg) break;   // the last head is written after the next copies start
         if (active) {
           const float inv = 1.0f / (l_run + __shfl_xor(l_run, 32));
           store_small(reinterpret_cast<bf16_t*>(a.O) + (((size_t)b * a.Hq + h) * S + r0) * (size_t)D, inv);
         }
       }
-      if (a.heads_per_wg > 1) continue;
-    } else {
-      h = h_first;
-      r0 = R * kChunk + 32 * wave;
-      active = r0 < S;
-      begin_head();
-      // Chunks below c_split are complete and fully visible to every wave of the workgroup
-      // (they lie left of the diagonal blocks of all 128 rows, and before a ragged end): the
-      // main loop runs only the test-free variant, two chunks per trip so that stages
-      // alternate without pointer arithmetic.  The few chunks from c_split on go through the
-      // masked variant.
-      const int c_split = CAUSAL ? min(2 * R, Sk / kLChunk) : Sk / kLChunk;
-      prefetch(kb0, vb0, 0);
-      int c = 0;
-      for (; c + 1 < c_split; c += 2) {
-        publish();
-        prefetch(kb1, vb1, c + 1);
-        step(kb0, vb0, c, 2, false);
-        publish();
-        if (c + 2 < n_chunk) prefetch(kb0, vb0, c + 2);
-        step(kb1, vb1, c + 1, 2, false);
-      }
-      // (one copy of the masked code: the stage is picked at run time, which only costs the
-      // compiler its proof that copy and reads touch different arrays, i.e. some overlap)
-      for (; c < n_chunk; ++c) {
-        publish();
-        bf16_t* kcur = (c & 1) ? kb1 : kb0;
-        bf16_t* vcur = (c & 1) ? vb1 : vb0;
-        if (c + 1 < n_chunk) prefetch((c & 1) ? kb0 : kb1, (c & 1) ? vb0 : vb1, c + 1);
-        tail_step(kcur, vcur, c);
-      }
+      const float inv = 1.0f / (l_run + __shfl_xor(l_run, 32));
+      bf16_t* Olast = reinterpret_cast<bf16_t*>(a.O) + (((size_t)b * a.Hq + h) * S + r0) * (size_t)D;
+      const bool act = active;
+      const int tn = locate(t + gridDim.x);
+      __syncthreads();          // every wave has finished reading the stages
+      if (tn >= 0) enter(tn);
+      if (act) store_small(Olast, inv);   // registers and the wave's own small buffer only
+      if (tn < 0) break;
+      t = tn;
+    }
+  } else {
+    // one tile per workgroup: (K/V tile u, head, row block R), heaviest row blocks first
+    const int bid = blockIdx.x;
+    const int slot = bid >> 3;
+    const int per_u = g * a.n_rblk;
+    u = (slot / per_u) * 8 + (bid & 7);   // ids equal mod 8 (one XCD) share K, V in its L2
+    if (u >= a.n_kvtiles) return;
+    h = (u % a.Hkv) * g + (slot % per_u) / a.n_rblk;
+    R = a.n_rblk - 1 - (slot % per_u) % a.n_rblk;
+    b = u / a.Hkv;
+    if (a.row_sel && a.row_sel[b] >= 0) return;
+    Ksrc = reinterpret_cast<const bf16_t*>(a.K) + (size_t)u * S * D;
+    Vsrc = reinterpret_cast<const bf16_t*>(a.V) + (size_t)u * S * D;
+    kptr = Ksrc + crow * D + 8 * kpiece;
+    vptr = Vsrc + crow * D + 8 * vpiece;
+    Sk = a.key_len ? min(max(a.key_len[b], 1), S) : S;
+    const int last_key = CAUSAL ? min(Sk, kChunk * (R + 1)) : Sk;
+    n_chunk = (last_key + kLChunk - 1) / kLChunk;
+    r0 = R * kChunk + 32 * wave;
+    active = r0 < S;
+    begin_head();
+    // Chunks below c_split are complete and fully visible to every wave of the workgroup
+    // (they lie left of the diagonal blocks of all 128 rows, and before a ragged end): the
+    // main loop runs only the test-free variant, two chunks per trip so that stages
+    // alternate without pointer arithmetic.  The few chunks from c_split on go through the
+    // masked variant.
+    const int c_split = CAUSAL ? min(2 * R, Sk / kLChunk) : Sk / kLChunk;
+    prefetch(kb0, vb0, 0);
+    int c = 0;
+    for (; c + 1 < c_split; c += 2) {
+      publish();
+      prefetch(kb1, vb1, c + 1);
+      step(kb0, vb0, c, 2, false);
+      publish();
+      if (c + 2 < n_chunk) prefetch(kb0, vb0, c + 2);
+      step(kb1, vb1, c + 1, 2, false);
+    }
+    // (one copy of the masked code: the stage is picked at run time, which only costs the
+    // compiler its proof that copy and reads touch different arrays, i.e. some overlap)
+    for (; c < n_chunk; ++c) {
+      publish();
+      bf16_t* kcur = (c & 1) ? kb1 : kb0;
+      bf16_t* vcur = (c & 1) ? vb1 : vb0;
+      if (c + 1 < n_chunk) prefetch((c & 1) ? kb0 : kb1, (c & 1) ? vb0 : vb1, c + 1);
+      tail_step(kcur, vcur, c);
     }
     __syncthreads();   // every wave is done with both stages: they now stage the output
     if (active) {
@@ -453,7 +470,7 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
       bf16_t* ost = wave == 0 ? kb0 : wave == 1 ? vb0 : wave == 2 ? kb1 : vb1;
       store_tile_bf16<D>(acc, inv, ost, Oh, lane);
     }
-  } while (RESIDENT && (bid += gridDim.x) < a.n_blocks);
+  }
 }
 
 // fp32 path (vector ALUs): one wave per (batch item, head, query row).
@@ -500,10 +517,10 @@ __global__ __launch_bounds__(kWave) void exact_f32_kernel(const ExactArgs a, int
 template <int D, bool CAUSAL, bool RESIDENT>
 static hipError_t launch_exact_bf16_r(ExactArgs a, dim3 grid, hipStream_t stream) {
   a.n_blocks = (int32_t)grid.x;
-  // routed launch: 32 workgroups per compute unit walk the tiles (enough of them for the
-  // hardware to even out an uneven mix of hits and misses; a multiple of 8 keeps the
-  // tile -> XCD assignment of the one-tile-per-workgroup launch)
-  if (RESIDENT && a.row_sel && grid.x > 8192u) grid.x = 8192u;
+  // resident launch: at most 32 workgroups per compute unit walk the tiles (enough of them for
+  // the hardware to even out an uneven mix of hits and misses -- fewer, longer-lived workgroups
+  // measured 2-5 % slower; a multiple of 8 keeps a workgroup's tiles on its own XCD)
+  if (RESIDENT && grid.x > 8192u) grid.x = 8192u;
   hipLaunchKernelGGL((exact_bf16_kernel<D, CAUSAL, RESIDENT>), grid, dim3(kThreads), 0, stream, a);
   return hipGetLastError();
 }
