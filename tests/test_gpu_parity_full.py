@@ -172,3 +172,72 @@ def test_workload_5_host_resident_maps_million_row_index(env, oracle_mod):
     # cannot pin 400 GiB: the entry count is reduced to 512 (entry size, index size, batch and
     # Zipf popularity are the workload's); search is checked on a sample of 24 queries.
     _run_workload(env, oracle_mod, 5, n_tiles=8, search_sample=24, host_entries=512)
+
+
+@pytest.mark.parametrize("cfg", [2, 4], ids=["llama-1b-shape", "long-sequence-shape"])
+def test_insert_and_projector_at_full_batch_size(env, oracle_mod, cfg):
+    """Database building at a workload's full batch shape: every item of the batch is computed,
+    remembered (packed layout) and found again; the oracle checks sampled tiles of the stored
+    maps and of the outputs, and the features come from the projector at the model's width."""
+    ac, synth, _ = env
+    dev = torch.device("cuda:0")
+    w = synth.WORKLOADS[cfg]
+    B, L, Hq, Hkv, S, D, E = (w.batch, w.n_layers, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim,
+                              w.emb_dim)
+    g = Hq // Hkv
+    M = B + 3
+    Q, K, V = synth.make_qkv(w, dev)
+
+    # features: projector on synthetic hidden states of the model's width
+    dm, hid = Hq * D, Hq * D // 4
+    gen = torch.Generator(device=dev).manual_seed(synth.seed_for(w, 9))
+    h = (torch.randn(B, 1, dm, generator=gen, device=dev) +
+         torch.randn(B, S, dm, generator=gen, device=dev)).to(torch.bfloat16)
+    W1 = torch.randn(hid, dm, generator=gen, device=dev) / dm ** 0.5
+    W2 = torch.randn(E, hid, generator=gen, device=dev) / hid ** 0.5
+    b1 = 0.1 * torch.randn(hid, generator=gen, device=dev)
+    b2 = 0.1 * torch.randn(E, generator=gen, device=dev)
+    pws = torch.empty(ac.attncache_project_workspace_bytes(B, dm, hid, E), dtype=torch.uint8, device=dev)
+    feat = torch.empty(B, E, dtype=torch.float16, device=dev)
+    ac.attncache_project(h, W1, b1, W2, b2, feat, pws)
+    torch.cuda.synchronize()
+    rows = [0, B // 2, B - 1]
+    want = oracle_mod.project(parity.to_np(h[rows]), parity.to_np(W1), parity.to_np(b1),
+                              parity.to_np(W2), parity.to_np(b2))
+    assert np.abs(parity.to_np(feat[rows]) - want).max() <= 2e-5 + 2.0 ** -11
+
+    # an empty database of M slots; the batch takes slots in a scrambled order
+    tile = ac.packed_tile_elems(S, w.causal)
+    maps = torch.zeros(M, L, Hq, tile, dtype=torch.bfloat16, device=dev)
+    emb = torch.zeros(M, E, dtype=torch.float16, device=dev)
+    db = ac.attncache_build_db(emb, maps, n_kv_heads=Hkv, head_dim=D, causal=w.causal, seq_len=S)
+    slot = torch.randperm(M, generator=torch.Generator().manual_seed(cfg))[:B].int().to(dev)
+    O = torch.full((B, L, Hq, S, D), 3.0, dtype=torch.bfloat16, device=dev)
+    ac.attncache_insert(db, Q, K, V, O, slot=slot, feat=feat)
+    torch.cuda.synchronize()
+    assert torch.isfinite(O.view(-1)[:: max(1, O.numel() // (1 << 24))].float()).all()
+
+    slot_h = slot.cpu().numpy()
+    for (b, l, hq) in _sample_tiles(list(range(B)), L, Hq, 6, cfg + 300):
+        ref_O, P = oracle_mod.attention_exact(parity.to_np(Q[b, l, hq]).reshape(1, 1, S, D),
+                                              parity.to_np(K[b, l, hq // g]).reshape(1, 1, S, D),
+                                              parity.to_np(V[b, l, hq // g]).reshape(1, 1, S, D),
+                                              causal=w.causal, return_map=True)
+        assert parity.max_abs_err(O[b, l, hq].contiguous(), ref_O[0, 0]) <= 2e-2, (b, l, hq)
+        stored = parity.unpack_map(parity.to_np(maps[int(slot_h[b]), l, hq]), S, w.causal)
+        parity.check_stored_map(stored, oracle_mod.round_maps(P, oracle_mod.ROUND_BF16)[0, 0])
+
+    # the same inputs now hit their own slots, and the reuse branch returns what was computed
+    ws = torch.empty(ac.attncache_workspace_bytes(db.desc, B, 1), dtype=torch.uint8, device=dev)
+    idx = torch.empty(B, 1, dtype=torch.int32, device=dev)
+    score = torch.empty(B, 1, dtype=torch.float32, device=dev)
+    hit = torch.empty(B, dtype=torch.int32, device=dev)
+    ac.attncache_search(db, feat, 1, 0.99, idx, score, hit, ws)
+    O2 = torch.full_like(O, 5.0)
+    ac.attncache_apply(db, hit, V, O2)
+    torch.cuda.synchronize()
+    assert torch.equal(hit, slot)
+    assert float((O2.float() - O.float()).abs().max()) <= 2e-2
+    unused = sorted(set(range(M)) - set(int(x) for x in slot_h))
+    assert torch.count_nonzero(maps[unused]) == 0 and torch.count_nonzero(emb[unused]) == 0
+    db.close()
