@@ -77,3 +77,19 @@ def test_product_path_does_not_touch_the_oracle():
         if f.endswith((".py", ".c")):
             src = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2510_25979_amd" not in src and "libattncache" not in src, f
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary must be usable from C: the header compiles as C99 with warnings as errors,
+    and a C translation unit can take the address of every declared entry point."""
+    import subprocess
+    names = _declared_symbols()
+    src = tmp_path / "use_abi.c"
+    body = "\n".join(f"  table[{i}] = (void (*)(void))&{n};" for i, n in enumerate(names))
+    src.write_text('#include "attncache.h"\n'
+                   f"void (*table[{len(names)}])(void);\n"
+                   "void fill(void) {\n" + body + "\n}\n"
+                   "int main(void) { attncache_db_desc d; (void)d; fill(); return AC_OK; }\n")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-c",
+                    "-I", os.path.join(ROOT, "include"), str(src), "-o", str(tmp_path / "use_abi.o")],
+                   check=True)
