@@ -149,8 +149,8 @@ __global__ __launch_bounds__(kThreads) void search_f16_kernel(const SearchArgs a
   }
 }
 
-// ---------------------------------------------------------------- phase 1, large batches
-// For more than 64 queries the roles are swapped: the QUERIES live in registers (each of the
+// ---------------------------------------------------------------- phase 1, query-stationary
+// For more than 64 queries, and for large databases at any batch size, the roles are swapped: the QUERIES live in registers (each of the
 // four waves keeps QPW blocks of 32 queries as MFMA column operands for the whole kernel) and
 // the database rows stream through LDS in chunks of 64 rows.  Every row operand read from LDS
 // feeds QPW MFMAs per wave and is shared by the four waves, so LDS traffic is 4x the HBM
@@ -285,22 +285,27 @@ __global__ __launch_bounds__(kThreads, 2) void search_f16_big_kernel(const Searc
           for (int v = 0; v < 16; ++v)
             if (rbase + 8 * (v >> 2) + (v & 3) >= row_end) acc[j][v] = -INFINITY;
       }
-      // The position is remembered as a code that is uniform over the wave, (32-row block of
-      // the group) * 16 + register: candidates then cost no vector registers; the row is
-      // decoded once at the end.
-      const int code = (ch * (kBigRows / 32) + rb) << 4;
+      // Only WHICH 32-row block holds a lane's best score is remembered (one compare and two
+      // selects per block and query block); the row inside that block is found by the
+      // finalising kernel, which re-scores the 32 rows of the one winning block per query.
+      // Looking the position up here was the expensive part: with 64 lanes and a few dozen
+      // blocks per workgroup some lane improves in nearly every block, so a wave-wide
+      // "did anyone improve" test almost never skipped the 48-instruction search.
+      // Blocks ascend with rb and ch, so the strict comparison keeps the lowest block among equals.
+      const int blk = ch * (kBigRows / 32) + rb;
 #pragma unroll
       for (int j = 0; j < QPW; ++j) {
         float mx = fmaxf(fmaxf(acc[j][0], acc[j][1]), acc[j][2]);
 #pragma unroll
         for (int v = 3; v < 15; v += 2) mx = fmaxf(fmaxf(mx, acc[j][v]), acc[j][v + 1]);
         mx = fmaxf(mx, acc[j][15]);
-        if (__any(mx > best_s[j])) {
-#pragma unroll
-          for (int v = 0; v < 16; ++v)
-            if (acc[j][v] > best_s[j]) { best_s[j] = acc[j][v]; best_i[j] = code + v; }
-        }
+        const bool up = mx > best_s[j];
+        best_s[j] = up ? mx : best_s[j];
+        best_i[j] = up ? blk : best_i[j];
       }
+      // the next block's products must not start before these comparisons are done: a second
+      // live set of result registers does not fit next to the query operands
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
   // own copies landed (they are counted like loads), then everybody's
@@ -337,8 +342,8 @@ __global__ __launch_bounds__(kThreads, 2) void search_f16_big_kernel(const Searc
   // combine the two lane halves; every wave owns its queries, nothing else to merge
 #pragma unroll
   for (int j = 0; j < QPW; ++j) {
-    if (best_i[j] != kIdxNone)   // code -> database row
-      best_i[j] = row_begin + 32 * (best_i[j] >> 4) + mfma_row(best_i[j] & 15, kh);
+    if (best_i[j] != kIdxNone)   // block -> its first database row (the stand-in for "the row")
+      best_i[j] = row_begin + 32 * best_i[j];
     const float so = __shfl_xor(best_s[j], 32);
     const int io = __shfl_xor(best_i[j], 32);
     if (ranks_before(so, io, best_s[j], best_i[j])) { best_s[j] = so; best_i[j] = io; }
@@ -420,6 +425,49 @@ __global__ __launch_bounds__(kThreads) void finalize_top1_kernel(const SearchArg
     a.idx[b] = i;
     a.score[b] = s;
     write_hit(a, b, s, i);
+  }
+}
+
+// k = 1 after the query-stationary kernel: the partial results name the first row of the
+// 32-row block that holds a group's maximum.  Best group first (lowest block on ties), then
+// the 32 rows of that one block are scored again (eight threads per row, fp32) and the best of
+// them (lowest row on ties) is the answer; the score reported is the matrix-core one of phase 1.
+__global__ __launch_bounds__(kThreads) void finalize_top1_block_kernel(const SearchArgs a) {
+  __shared__ float red_s[4];
+  __shared__ int red_i[4];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  float s = -INFINITY;
+  int i = kIdxNone;
+  for (int gi = tid; gi < a.G; gi += kThreads) {
+    const float so = a.part_s[(size_t)b * a.G + gi];
+    const int io = a.part_i[(size_t)b * a.G + gi];
+    if (ranks_before(so, io, s, i)) { s = so; i = io; }
+  }
+  block_argmax(s, i, red_s, red_i);
+  const f16_t* q = reinterpret_cast<const f16_t*>(a.q) + (size_t)b * a.E;
+  const int row = i + (tid >> 3), part = tid & 7;
+  float rs = -INFINITY;
+  int ri = kIdxNone;
+  if (i != kIdxNone && row < a.N) {
+    const f16_t* e = reinterpret_cast<const f16_t*>(a.emb) + (size_t)row * a.E;
+    float acc = 0.f;
+    for (int c = 8 * part; c < a.E; c += 64) {   // 16-byte pieces, eight threads side by side
+      const f16x8 ev = *reinterpret_cast<const f16x8*>(e + c);
+      const f16x8 qv = *reinterpret_cast<const f16x8*>(q + c);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) acc = fmaf((float)ev[t], (float)qv[t], acc);
+    }
+    acc += __shfl_xor(acc, 1);
+    acc += __shfl_xor(acc, 2);
+    acc += __shfl_xor(acc, 4);
+    rs = acc;
+    ri = row;
+  }
+  block_argmax(rs, ri, red_s, red_i);
+  if (tid == 0) {
+    a.idx[b] = ri;
+    a.score[b] = s;
+    write_hit(a, b, s, ri);
   }
 }
 
@@ -634,7 +682,9 @@ hipError_t launch_search(const SearchLaunch& p, hipStream_t stream) {
     if (e != hipSuccess) return e;
   }
 
-  if (p.k == 1) {
+  if (p.k == 1 && mode == kModeMfmaBig) {
+    hipLaunchKernelGGL(finalize_top1_block_kernel, dim3((unsigned)p.B), dim3(kThreads), 0, stream, a);
+  } else if (p.k == 1) {
     hipLaunchKernelGGL(finalize_top1_kernel, dim3((unsigned)p.B), dim3(kThreads), 0, stream, a);
   } else {
     const size_t lds = (size_t)p.E * 4 + (size_t)p.k * 4;

@@ -313,6 +313,25 @@ def test_search_matches_oracle(ac, oracle_mod, case):
     assert exempt <= max(1, B * k // 50), exempt
 
 
+def test_search_large_database_duplicates_give_the_lowest_row(ac, oracle_mod):
+    # the query-stationary kernel remembers only the winning 32-row block and the finalising
+    # kernel re-scores it: copies of the best row in the same block, in another block of the
+    # same group and in another group must all lose to the lowest row
+    N, E, B = 66000, 128, 70
+    g = _gen(4242)
+    raw = torch.randn(N, E, generator=g)
+    emb = (raw / raw.norm(dim=-1, keepdim=True)).half()
+    rows = 100 + 200 * torch.randperm(100, generator=g)[:B]      # far enough apart not to collide
+    for r in rows.tolist():
+        emb[r + 3] = emb[r]            # usually the same 32-row block
+        emb[r + 64] = emb[r]           # the next chunk of the same group
+        emb[r + 40000] = emb[r]        # a different group
+    q = emb[rows].clone()
+    idx, score, hit = _run_search(ac, emb, q, 1, 0.9, ac.AC_IP)
+    assert torch.equal(idx[:, 0].cpu().long(), rows)
+    parity.check_search(oracle_mod, q, emb, 1, 0.9, ac.AC_IP, None, idx, score, hit)
+
+
 def test_search_ties_take_the_lowest_index(ac, oracle_mod):
     g = _gen(9)
     N, E = 2000, 256
