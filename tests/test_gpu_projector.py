@@ -75,6 +75,8 @@ CASES = [
     (70, 16, 4096, 1024, 128, torch.bfloat16, torch.float16, True, True, True),    # 8B-shaped width, 3 query tiles
     (1, 1, 8, 8, 8, torch.float32, torch.float32, False, False, True),             # smallest sizes accepted
     (130, 9, 520, 264, 2048, torch.bfloat16, torch.float32, True, True, True),     # widest feature vector
+    (3, 1000, 264, 136, 64, torch.bfloat16, torch.float16, True, True, True),      # long sentences: several pooling rounds
+    (2, 300, 128, 64, 32, torch.float32, torch.float32, False, False, True),       # the same with fp32 hidden states
 ]
 
 
