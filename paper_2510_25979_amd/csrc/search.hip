@@ -389,7 +389,7 @@ __global__ __launch_bounds__(kThreads) void search_valu_kernel(const SearchArgs 
   const int r = gidx * a.rows_per_wg + threadIdx.x;
   float s = -INFINITY;
   int i = kIdxNone;
-  if (threadIdx.x < a.rows_per_wg && r < a.N) {
+  if ((int)threadIdx.x < a.rows_per_wg && r < a.N) {
     s = row_score(reinterpret_cast<const T*>(a.emb) + (size_t)r * a.E, qf, a.E, a.metric);
     i = r;
   }
