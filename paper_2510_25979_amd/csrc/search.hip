@@ -166,7 +166,7 @@ __global__ __launch_bounds__(kThreads) void search_f16_kernel(const SearchArgs a
 constexpr int kBigRows = 64;   // database rows per LDS chunk
 
 template <int KSMAX, int QPW>
-__global__ __launch_bounds__(kThreads, 2) void search_f16_big_kernel(const SearchArgs a) {
+__global__ __launch_bounds__(kThreads, (KSMAX == 32 ? 1 : 2)) void search_f16_big_kernel(const SearchArgs a) {
   constexpr int E = 16 * KSMAX;               // this kernel is built for E = 128, 256, 512
   constexpr int EQ = E / 8;                   // 16-byte pieces per row
   constexpr int NDMA = kBigRows * EQ / kWave / 4;   // copy instructions per wave and chunk
