@@ -189,7 +189,11 @@ int32_t attncache_destroy_db(attncache_db *db);
  *             -1 for a miss.
  *   ws        DEVICE workspace of ws_bytes >= attncache_workspace_bytes().
  *
- * B == 0 is a no-op.  Scores are accumulated in fp32.
+ * B == 0 is a no-op.  Scores are accumulated in fp32; the order of the
+ * additions depends on the kernel that serves the shape, so two rows whose
+ * exact scores differ by less than about 1e-6 relative may come out in
+ * either order (rows with bit-identical feature vectors never do: the lower
+ * index wins).
  */
 int32_t attncache_search(const attncache_db *db, const void *q, int32_t B,
                          int32_t k, float threshold, int32_t *idx,
