@@ -77,6 +77,10 @@ def main():
                     help="also time the feature projector in front of the search (hidden states "
                          "[B][S][Hq*D] bf16, hidden width a quarter of that, synthetic weights) and "
                          "report it as `projector`; it is not part of the timed step")
+    ap.add_argument("--index-probe", action="store_true",
+                    help="also time attncache_search alone on the over-HBM workload's index (1,000,000 x "
+                         "256 fp16 feature vectors, 256 and 64 queries) and report it as "
+                         "`large_index_search`; not part of the timed step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 1 GiB device copy (a kernel of known HBM traffic "
@@ -228,6 +232,44 @@ def main():
                      "launches_per_step": 4 * L if w.k == 1 else 5 * L}
         del Ql, Kl, Vl, Ol
 
+    # ------------------------- search alone on the million-row index of the over-HBM workload
+    index_probe = None
+    if args.index_probe:
+        w5 = synth.WORKLOADS[5]
+        gi = torch.Generator(device=dev).manual_seed(synth.seed_for(w5, 1))
+        big = torch.randn(w5.n_emb, w5.emb_dim, generator=gi, device=dev)
+        big = (big / big.norm(dim=-1, keepdim=True)).half()
+        tiny_maps = torch.zeros(16, 1, 1, 32, 32, dtype=torch.bfloat16, device=dev)
+        big_db = ac.attncache_build_db(big, tiny_maps, n_kv_heads=1, head_dim=64,
+                                       map_of=(torch.arange(w5.n_emb, device=dev) % 16).int())
+        index_probe = {"rows": w5.n_emb, "dim": w5.emb_dim, "dtype": "f16"}
+        for nq in (256, 64):
+            rows = torch.randint(0, w5.n_emb, (nq,), generator=gi, device=dev)
+            qq = big[rows].float() + 0.005 * torch.randn(nq, w5.emb_dim, generator=gi, device=dev)
+            qq = (qq / qq.norm(dim=-1, keepdim=True)).half()
+            wsb = torch.empty(ac.attncache_workspace_bytes(big_db.desc, nq, 1), dtype=torch.uint8,
+                              device=dev)
+            i_b = torch.empty(nq, 1, dtype=torch.int32, device=dev)
+            s_b = torch.empty(nq, 1, dtype=torch.float32, device=dev)
+            h_b = torch.empty(nq, dtype=torch.int32, device=dev)
+            for _ in range(max(1, args.warmup)):
+                ac.attncache_search(big_db, qq, 1, w5.theta, i_b, s_b, h_b, wsb)
+            torch.cuda.synchronize()
+            assert torch.equal(i_b[:, 0].long(), rows), "planted rows of the large index not found"
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                ac.attncache_search(big_db, qq, 1, w5.theta, i_b, s_b, h_b, wsb)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / args.steps * 1e3
+            index_probe[f"B{nq}"] = {
+                "us": us, "qps": nq / us * 1e6,
+                "hbm_frac": 2.0 * w5.n_emb * w5.emb_dim / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                "mfma_frac": 2.0 * nq * w5.n_emb * w5.emb_dim / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+        big_db.close()
+        del big, tiny_maps
+
     # ------------------------- feature projector in front of the search (Algorithm 1), on request
     projector = None
     if args.projector and w.emb_dtype == "f16":
@@ -340,6 +382,8 @@ def main():
         result["per_layer_mode"] = per_layer
     if projector is not None:
         result["projector"] = projector
+    if index_probe is not None:
+        result["large_index_search"] = index_probe
 
     # ------------------------------------------- CPU oracle on a bounded sample (reported only)
     if not args.no_cpu_baseline:
