@@ -284,14 +284,15 @@ __global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const Appl
 
   // 16-byte operand piece of column step ks (16 columns, counted from column 0) for this lane:
   // map row 32 rb32 + il, columns 16 ks + 8 kh .. + 8
+  // (32-bit element offsets from the tile's base, which is uniform over the workgroup: the
+  // loads then take a scalar base and one offset register instead of 64-bit lane addresses)
+  const unsigned piece_row = PACKED
+      ? (unsigned)((CAUSAL ? packed_prefix(2 * rb32 + (il >> 4)) : (2 * rb32 + (il >> 4)) * n32) * 512 +
+                   (kh * 16 + (il & 15)) * 8)
+      : (unsigned)((32 * rb32 + il) * S + 8 * kh);
   auto piece = [&](int ks) -> const u32x4* {
-    if (PACKED) {
-      const int r16 = 2 * rb32 + (il >> 4);
-      const int blk = (CAUSAL ? packed_prefix(r16) : r16 * n32) + (ks >> 1);
-      return reinterpret_cast<const u32x4*>(At + (size_t)blk * 512 +
-                                            ((2 * (ks & 1) + kh) * 16 + (il & 15)) * 8);
-    }
-    return reinterpret_cast<const u32x4*>(At + (size_t)(32 * rb32 + il) * S + 16 * ks + 8 * kh);
+    const unsigned off = PACKED ? piece_row + (unsigned)ks * 256u : piece_row + (unsigned)ks * 16u;
+    return reinterpret_cast<const u32x4*>(At + off);
   };
   // column steps of chunk c this wave needs
   auto steps = [&](int c) {
@@ -318,9 +319,11 @@ __global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const Appl
   // end of V (ragged last chunk) repeat the last row: finite values that are never multiplied.
   const int slot0 = kWave * wave + lane;
   const unsigned copy_off = (unsigned)((slot0 / PPR) * D + 8 * ((slot0 % PPR) ^ (2 * ((slot0 / PPR) & kSwz))));
+  const bf16_t* vrun = Vsrc;   // chunk after chunk, in order: a running (scalar) source pointer
   auto copy_v = [&](bf16_t* buf, int c) {
     const int nj = min(kChunk, S - c * kChunk);
-    const bf16_t* src = Vsrc + (size_t)c * kChunk * D;
+    const bf16_t* src = vrun;
+    vrun += kChunk * D;
     if (nj == kChunk) {
 #pragma unroll
       for (int i = 0; i < NCOPY; ++i)
