@@ -219,14 +219,16 @@ __global__ __launch_bounds__(kThreads, (KSMAX == 32 ? 1 : 2)) void search_f16_bi
   // the same for a chunk that reaches beyond the database: rows past the end repeat the last
   // row (they are masked when compared)
   auto copy_in_clamped = [&](f16_t* buf, int ch) {
+    const int first = row_begin + ch * kBigRows;
+    const f16_t* src = emb + (size_t)first * E;   // uniform; lanes add a small 32-bit offset
+    const int last = a.N - 1 - first;
 #pragma unroll
     for (int i = 0; i < NDMA; ++i) {
       const int slot = kWave * (wave + 4 * i) + lane;
       const int row = slot / EQ, pos = slot % EQ;
-      const int piece = pos ^ (row & 15);
-      const int r = min(row_begin + ch * kBigRows + row, a.N - 1);
-      __builtin_amdgcn_global_load_lds(emb + (size_t)r * E + 8 * piece,
-                                       buf + kWave * (wave + 4 * i) * 8, 16, 0, 0);
+      const unsigned off = (unsigned)(min(row, last) * E + 8 * (pos ^ (row & 15)));
+      const f16_t* piece = src + off;
+      __builtin_amdgcn_global_load_lds(piece, buf + kWave * (wave + 4 * i) * 8, 16, 0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
   };
