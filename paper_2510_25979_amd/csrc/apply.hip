@@ -241,6 +241,8 @@ void apply_bf16_kernel(const ApplyArgs a) {
 // Rows are stored unpadded; 16-byte piece p of key row r sits at position p ^ 2 (r & (D/16 - 1)), which
 // spreads the four key rows one group touches over distinct banks; the copy applies the
 // swizzle by choosing which global piece each lane fetches.
+constexpr int kOutStride = 64 + 4;   // row stride of the 16 x 64 output staging passes
+
 template <int D, bool CAUSAL, bool PACKED>
 __global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const ApplyArgs a) {
   constexpr int PPR = D / 8;                       // 16-byte pieces per V row
@@ -248,14 +250,25 @@ __global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const Appl
   constexpr int kSwz = PPR / 2 - 1;                // swizzle mask: 2 (r & kSwz) < PPR
   __shared__ __attribute__((aligned(16))) bf16_t vb0[kChunk * D];
   __shared__ __attribute__((aligned(16))) bf16_t vb1[kChunk * D];
+  // Causal maps at head_dim 64: a workgroup takes a PAIR of row blocks (see below).  Its
+  // results then leave through a small wave-private buffer, 16 rows x 64 columns per pass,
+  // because the V buffers stay in use.
+  constexpr bool PAIRED = CAUSAL && D == 64;
+  __shared__ __attribute__((aligned(16))) bf16_t ost_small[PAIRED ? 4 * 16 * kOutStride : 8];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: branches on it stay uniform
   const int il = lane & 31, kh = lane >> 5;
 
   const int bid = blockIdx.x;
-  const int tile = (bid >> 3) / a.n_rblk * 8 + (bid & 7);
-  const int R = a.n_rblk - 1 - (bid >> 3) % a.n_rblk;
+  // PAIRED: row blocks are handled in pairs (n_rblk - 1 - p, then p): under the causal mask
+  // their chunk counts add up to n_rblk + 1 for every p, so all workgroups of a launch carry
+  // equal work, and the chunk pipeline runs on across the switch (one fill per workgroup, not
+  // two): 61 -> 70 % of HBM peak at S = 1024, D = 64.  At D = 128 the V copies, not the short
+  // workgroups, are the limit and pairing gains nothing; dense maps have equal work anyway.
+  const int n_pairs = PAIRED ? (a.n_rblk + 1) >> 1 : a.n_rblk;
+  const int tile = (bid >> 3) / n_pairs * 8 + (bid & 7);
+  const int pair = (bid >> 3) % n_pairs;
   if (tile >= a.n_tiles) return;
   const int h = tile % a.Hq;
   const int l = (tile / a.Hq) % a.Lc;
@@ -278,39 +291,47 @@ __global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const Appl
   const bf16_t* At = reinterpret_cast<const bf16_t*>(a.maps) +
                      (((size_t)entry * a.L + (a.layer_begin + l)) * a.Hq + h) * tile_elems;
 
-  const int rb32 = 4 * R + wave;            // 32-row block of this wave
-  const bool active = 32 * rb32 < S;
-  const int n_chunk = CAUSAL ? R + 1 : (S + kChunk - 1) / kChunk;
+  const int R_hi = a.n_rblk - 1 - pair, R_lo = PAIRED ? pair : R_hi;   // heaviest first
+  const int n_hi = CAUSAL ? R_hi + 1 : (S + kChunk - 1) / kChunk;
+  const int n_total = n_hi + (R_hi != R_lo ? (CAUSAL ? R_lo + 1 : n_hi) : 0);
+  // chunk t of the workgroup's walk: its row block and its chunk index within that block
+  auto row_block = [&](int t) { return t < n_hi ? R_hi : R_lo; };
+  auto chunk_of = [&](int t) { return t < n_hi ? t : t - n_hi; };
 
   // 16-byte operand piece of column step ks (16 columns, counted from column 0) for this lane:
-  // map row 32 rb32 + il, columns 16 ks + 8 kh .. + 8
+  // map row 32 rb32 + il, columns 16 ks + 8 kh .. + 8, rb32 = 4 R + wave being this wave's rows
   // (32-bit element offsets from the tile's base, which is uniform over the workgroup: the
   // loads then take a scalar base and one offset register instead of 64-bit lane addresses)
-  const unsigned piece_row = PACKED
+  auto piece_row_of = [&](int R) {
+    const int rb32 = 4 * R + wave;
+    return PACKED
       ? (unsigned)((CAUSAL ? packed_prefix(2 * rb32 + (il >> 4)) : (2 * rb32 + (il >> 4)) * n32) * 512 +
                    (kh * 16 + (il & 15)) * 8)
       : (unsigned)((32 * rb32 + il) * S + 8 * kh);
-  auto piece = [&](int ks) -> const u32x4* {
+  };
+  const unsigned piece_row_hi = piece_row_of(R_hi), piece_row_lo = piece_row_of(R_lo);
+  auto piece = [&](int R, int ks) -> const u32x4* {
+    const unsigned piece_row = R == R_hi ? piece_row_hi : piece_row_lo;
     const unsigned off = PACKED ? piece_row + (unsigned)ks * 256u : piece_row + (unsigned)ks * 16u;
     return reinterpret_cast<const u32x4*>(At + off);
   };
   // column steps of chunk c this wave needs
-  auto steps = [&](int c) {
-    if (!active) return 0;
+  auto steps = [&](int R, int c) {
+    if (32 * (4 * R + wave) >= S) return 0;
     const int nk = min(kChunk, S - c * kChunk) >> 4;
     return (CAUSAL && c == R) ? min(nk, 2 * (wave + 1)) : nk;
   };
-  auto full = [&](int c) {   // uniform over the workgroup: every wave takes all 8 steps
+  auto full = [&](int R, int c) {   // uniform over the workgroup: every wave takes all 8 steps
     return !(CAUSAL && c == R) && S - c * kChunk >= kChunk && 32 * (4 * R + 3) < S;
   };
   // map pieces of chunk c into am.  Every lane loads 8 pieces whatever it needs: a step beyond
   // the wave's last one repeats that last piece (same cache lines, no extra memory traffic,
   // never multiplied), which keeps the loads free of per-wave control flow.
-  auto issue = [&](int c, u32x4 (&am)[8]) {
-    const int nks = steps(c);
+  auto issue = [&](int R, int c, u32x4 (&am)[8]) {
+    const int nks = steps(R, c);
     if (nks == 0) return;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) am[ks] = *piece(8 * c + min(ks, nks - 1));
+    for (int ks = 0; ks < 8; ++ks) am[ks] = *piece(R, 8 * c + min(ks, nks - 1));
   };
   // copy key rows [128 c, 128 c + nj) of V into buf: instruction k = wave + 4 i fills LDS slots
   // [64 k, 64 k + 64) (slot = row * PPR + position), i.e. rows [k 64/PPR, (k + 1) 64/PPR).
@@ -376,8 +397,8 @@ __global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const Appl
   };
   // Products of chunk c.  The scheduling fences keep the compiler from hoisting every operand
   // read of a chunk in front of the first product (more registers than the file has).
-  auto compute = [&](const bf16_t* buf, int c, const u32x4 (&am)[8]) {
-    if (full(c)) {
+  auto compute = [&](const bf16_t* buf, int R, int c, const u32x4 (&am)[8]) {
+    if (full(R, c)) {
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
@@ -386,7 +407,7 @@ __global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const Appl
         __builtin_amdgcn_sched_barrier(0);
       }
     } else {
-      const int nks = steps(c);
+      const int nks = steps(R, c);
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
         if (ks < nks) {
@@ -407,30 +428,85 @@ __global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const Appl
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
   };
-  auto prefetch = [&](bf16_t* buf, int c, u32x4 (&am)[8]) {
-    copy_v(buf, c);
-    issue(c, am);
+  auto prefetch = [&](bf16_t* buf, int t, u32x4 (&am)[8]) {
+    if (t == n_hi) vrun = Vsrc;   // the second row block starts over at the first keys
+    copy_v(buf, chunk_of(t));
+    issue(row_block(t), chunk_of(t), am);
     __builtin_amdgcn_sched_barrier(0);
+  };
+  // after the last chunk of a row block: the wave's 32 x D result leaves in 16 x 64 passes
+  // through its small private buffer (every global store covers whole 128-byte lines), and
+  // the accumulator starts over.  No barrier: the V buffers are not touched.
+  auto finish = [&](int t) {
+    if (!PAIRED) return;   // one row block per workgroup: stored after the loop, through the V buffers
+    if (t + 1 != n_hi && t + 1 != n_total) return;
+    const int rb32 = 4 * row_block(t) + wave;
+    if (32 * rb32 < S) {
+      bf16_t* dst = reinterpret_cast<bf16_t*>(a.O) +
+                    ((((size_t)b * a.Lc + l) * a.Hq + h) * S + 32 * rb32) * (size_t)D;
+      bf16_t* ost = ost_small + wave * (16 * kOutStride);
+#pragma unroll
+      for (int rh = 0; rh < 2; ++rh)
+#pragma unroll
+        for (int dh = 0; dh < D / 64; ++dh) {
+          if ((il >> 4) == rh) {
+#pragma unroll
+            for (int dbp = 0; dbp < 2; ++dbp)
+#pragma unroll
+              for (int vq = 0; vq < 4; ++vq) {
+                const f32x16& r = acc[2 * dh + dbp];
+                u32x2 w;
+                w.x = pack_bf16(r[4 * vq], r[4 * vq + 1]);
+                w.y = pack_bf16(r[4 * vq + 2], r[4 * vq + 3]);
+                *reinterpret_cast<u32x2*>(ost + (il & 15) * kOutStride + 32 * dbp + 8 * vq + 4 * kh) = w;
+              }
+          }
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+          for (int it = 0; it < 2; ++it) {
+            const int p = it * kWave + lane;
+            const int row = p >> 3, c8 = p & 7;
+            const u32x2* sp = reinterpret_cast<const u32x2*>(ost + row * kOutStride + 8 * c8);
+            u32x2 lo = sp[0], hi = sp[1];
+            __builtin_nontemporal_store(
+                u32x4{lo.x, lo.y, hi.x, hi.y},
+                reinterpret_cast<u32x4*>(dst + (size_t)(16 * rh + row) * D + 64 * dh + 8 * c8));
+          }
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+        }
+    }
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
   };
 
   u32x4 am0[8], am1[8];
   prefetch(vb0, 0, am0);
-  for (int c = 0; c < n_chunk; c += 2) {
+  for (int t = 0; t < n_total; t += 2) {
     publish();
-    if (c + 1 < n_chunk) prefetch(vb1, c + 1, am1);
-    compute(vb0, c, am0);
-    if (c + 1 < n_chunk) {
+    if (t + 1 < n_total) prefetch(vb1, t + 1, am1);
+    compute(vb0, row_block(t), chunk_of(t), am0);
+    finish(t);
+    if (t + 1 < n_total) {
       publish();
-      if (c + 2 < n_chunk) prefetch(vb0, c + 2, am0);
-      compute(vb1, c + 1, am1);
+      if (t + 2 < n_total) prefetch(vb0, t + 2, am0);
+      compute(vb1, row_block(t + 1), chunk_of(t + 1), am1);
+      finish(t + 1);
     }
   }
-  __syncthreads();   // every wave is done with both V buffers: they now stage the output
-  if (active) {
-    bf16_t* dst = reinterpret_cast<bf16_t*>(a.O) +
-                  ((((size_t)b * a.Lc + l) * a.Hq + h) * S + 32 * rb32) * (size_t)D;
-    bf16_t* ost = ((wave & 2) ? vb1 : vb0) + (wave & 1) * (32 * (D + 4));
-    store_tile_bf16<D>(acc, 1.0f, ost, dst, lane);
+  if constexpr (!PAIRED) {
+    __syncthreads();   // every wave is done with both V buffers: they now stage the output
+    const int rb32 = 4 * R_hi + wave;
+    if (32 * rb32 < S) {
+      bf16_t* dst = reinterpret_cast<bf16_t*>(a.O) +
+                    ((((size_t)b * a.Lc + l) * a.Hq + h) * S + 32 * rb32) * (size_t)D;
+      bf16_t* ost = ((wave & 2) ? vb1 : vb0) + (wave & 1) * (32 * (D + 4));
+      store_tile_bf16<D>(acc, 1.0f, ost, dst, lane);
+    }
   }
 }
 
@@ -514,18 +590,21 @@ static hipError_t launch_bf16_dc(const ApplyArgs& a, dim3 grid, bool packed, boo
 }
 
 template <int D, bool CAUSAL, bool PACKED>
-static hipError_t launch_long(const ApplyArgs& a, dim3 grid, hipStream_t stream) {
+static hipError_t launch_long(const ApplyArgs& a, int tiles8, hipStream_t stream) {
+  // causal maps at head_dim 64: a workgroup takes a pair of row blocks (see the kernel)
+  const int per_tile = (CAUSAL && D == 64) ? (a.n_rblk + 1) / 2 : a.n_rblk;
+  const dim3 grid((unsigned)(tiles8 * per_tile));
   hipLaunchKernelGGL((apply_bf16_long_kernel<D, CAUSAL, PACKED>), grid, dim3(kThreads), 0, stream, a);
   return hipGetLastError();
 }
 
 template <int D>
-static hipError_t launch_long_d(const ApplyArgs& a, dim3 grid, bool causal, bool packed,
+static hipError_t launch_long_d(const ApplyArgs& a, int tiles8, bool causal, bool packed,
                                 hipStream_t stream) {
-  if (causal) return packed ? launch_long<D, true, true>(a, grid, stream)
-                            : launch_long<D, true, false>(a, grid, stream);
-  return packed ? launch_long<D, false, true>(a, grid, stream)
-                : launch_long<D, false, false>(a, grid, stream);
+  if (causal) return packed ? launch_long<D, true, true>(a, tiles8, stream)
+                            : launch_long<D, true, false>(a, tiles8, stream);
+  return packed ? launch_long<D, false, true>(a, tiles8, stream)
+                : launch_long<D, false, false>(a, tiles8, stream);
 }
 
 // Host launcher.  Shapes were validated by the caller (api.hip).
@@ -552,8 +631,8 @@ hipError_t launch_apply(const ApplyLaunch& p, hipStream_t stream) {
   const int tiles8 = (a.n_tiles + 7) / 8 * 8;
   const dim3 grid((unsigned)(tiles8 * a.n_rblk));
   if (a.n_rblk > 1)   // long rows: 32-row blocks per wave, full-rate matrix instruction
-    return p.D == 64 ? launch_long_d<64>(a, grid, p.causal, p.packed, stream)
-                     : launch_long_d<128>(a, grid, p.causal, p.packed, stream);
+    return p.D == 64 ? launch_long_d<64>(a, tiles8, p.causal, p.packed, stream)
+                     : launch_long_d<128>(a, tiles8, p.causal, p.packed, stream);
   // a workgroup that walks several heads prefetches the next head's map pieces
   const bool prefetch = a.heads_per_wg > 1;
   if (p.D == 64)

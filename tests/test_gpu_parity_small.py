@@ -44,6 +44,9 @@ APPLY_CASES = [
     (2, 2, 1, 2, 1, 416, 64, True, 0, 1, torch.bfloat16),     # four row blocks, ragged, 2 heads per V
     (1, 2, 1, 1, 1, 1024, 128, True, 0, 1, torch.bfloat16),   # the long-sequence shape, one head
     (2, 2, 1, 2, 2, 224, 128, False, 0, 1, torch.bfloat16),   # dense maps, two chunks, ragged
+    (2, 3, 1, 2, 2, 320, 64, True, 0, 1, torch.bfloat16),     # paired row blocks: (2, 0) and the middle one alone
+    (2, 2, 1, 2, 1, 160, 64, True, 0, 1, torch.bfloat16),     # one pair, ragged second block
+    (1, 2, 1, 2, 2, 1024, 64, True, 0, 1, torch.bfloat16),    # four pairs of row blocks
 ]
 
 
