@@ -667,6 +667,34 @@ def test_host_resident_maps_are_cached_across_batches(ac, oracle_mod):
     db.close()
 
 
+def test_empty_batches_and_all_miss_batches_touch_nothing(ac):
+    M, L, Hq, Hkv, S, D, E = 4, 1, 2, 2, 32, 64, 32
+    emb = torch.randn(M, E).half().cuda()
+    maps = torch.zeros(M, L, Hq, S, S, dtype=torch.bfloat16, device="cuda")
+    db = ac.attncache_build_db(emb, maps, n_kv_heads=Hkv, head_dim=D)
+    ws = torch.empty(max(256, ac.attncache_workspace_bytes(db.desc, 1, 1)), dtype=torch.uint8, device="cuda")
+    z = lambda *shape, dt=torch.bfloat16: torch.zeros(*shape, dtype=dt, device="cuda")
+    # B = 0 through every entry point
+    ac.attncache_search(db, z(0, E, dt=torch.float16), 1, 0.5, z(0, 1, dt=torch.int32),
+                        z(0, 1, dt=torch.float32), z(0, dt=torch.int32), ws)
+    ac.attncache_apply(db, z(0, dt=torch.int32), z(0, L, Hkv, S, D), z(0, L, Hq, S, D))
+    ac.attention_exact(z(0, Hq, S, D), z(0, Hkv, S, D), z(0, Hkv, S, D), z(0, Hq, S, D))
+    ac.attncache_insert(db, z(0, L, Hq, S, D), z(0, L, Hkv, S, D), z(0, L, Hkv, S, D), z(0, L, Hq, S, D),
+                        slot=z(0, dt=torch.int32))
+    # a batch of misses only: the reuse branch writes nothing; a batch of hits only: neither does
+    # the recompute branch
+    B = 3
+    V = torch.randn(B, L, Hkv, S, D, device="cuda").to(torch.bfloat16)
+    O = torch.full((B, L, Hq, S, D), 7.0, dtype=torch.bfloat16, device="cuda")
+    ac.attncache_apply(db, torch.full((B,), -1, dtype=torch.int32, device="cuda"), V, O)
+    ac.attention_exact(V.view(B, Hq, S, D), V.view(B, Hkv, S, D), V.view(B, Hkv, S, D), O.view(B, Hq, S, D),
+                       row_sel=torch.zeros(B, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    assert (O == 7.0).all()
+    assert torch.count_nonzero(maps) == 0
+    db.close()
+
+
 def test_error_codes(ac):
     emb = torch.zeros(64, 128, dtype=torch.float16, device="cuda")
     maps = torch.zeros(64, 1, 2, 32, 32, dtype=torch.bfloat16, device="cuda")
