@@ -62,6 +62,9 @@ extern "C" {
 
 #define AC_MAX_K 64
 
+/* Size of the built-in search workspace of attncache_search_static. */
+#define AC_STATIC_SCRATCH_BYTES (4u << 20)
+
 /* ---- database ---------------------------------------------------------- */
 
 /*
@@ -199,6 +202,30 @@ int32_t attncache_search(const attncache_db *db, const void *q, int32_t B,
                          int32_t k, float threshold, int32_t *idx,
                          float *score, int32_t *hit, void *ws, size_t ws_bytes,
                          void *stream);
+
+/*
+ * attncache_search for callers that cannot allocate or bring a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels and bit-identical results, but
+ * the workspace is a fixed array of AC_STATIC_SCRATCH_BYTES (4 MiB) inside
+ * the library's code object: every GPU the library runs on holds one copy
+ * until the process ends.  The call allocates and frees nothing.
+ *
+ * Limit: shapes whose attncache_workspace_bytes() exceeds
+ * AC_STATIC_SCRATCH_BYTES return AC_ERR_WORKSPACE (k = 1 fits up to about
+ * 1,000 queries on a million-row index; large k on a large index does not).
+ * All calls on one GPU share the one array: calls that overlap in time on
+ * the same GPU (two streams, two threads, two handles) race and give wrong
+ * results -- order them.  Nothing in it has to start at zero (every word
+ * that is read was written by the same call before).  The array's device
+ * address is looked up once per GPU, at attncache_build_db or at the first
+ * call with that GPU current; when the first call of a process is to be
+ * captured into a graph, build the handle beforehand (that is the norm).
+ */
+int32_t attncache_search_static(const attncache_db *db, const void *q,
+                                int32_t B, int32_t k, float threshold,
+                                int32_t *idx, float *score, int32_t *hit,
+                                void *stream);
 
 /*
  * Algorithm 2, reuse branch: O[b][l][h] = A[hit[b]][layer_begin+l][h] . V[b][l][h/g]

@@ -26,7 +26,7 @@ _DTYPE_CODE = {torch.float32: AC_F32, torch.float16: AC_F16, torch.bfloat16: AC_
 
 SYMBOLS = ["attncache_workspace_bytes", "attncache_map_entry_bytes", "attncache_pack_maps",
            "attncache_build_db", "attncache_destroy_db",
-           "attncache_search", "attncache_apply", "attention_exact", "attncache_insert",
+           "attncache_search", "attncache_search_static", "attncache_apply", "attention_exact", "attncache_insert",
            "attncache_cache_stats", "attncache_cache_reset",
            "attncache_project_workspace_bytes", "attncache_project", "attncache_status_string",
            "attncache_last_hip_error", "attncache_version"]
@@ -76,6 +76,8 @@ def lib():
         L.attncache_destroy_db.argtypes = [vp]
         L.attncache_search.restype = i32
         L.attncache_search.argtypes = [vp, vp, i32, i32, f32, vp, vp, vp, vp, sz, vp]
+        L.attncache_search_static.restype = i32
+        L.attncache_search_static.argtypes = [vp, vp, i32, i32, f32, vp, vp, vp, vp]
         L.attncache_apply.restype = i32
         L.attncache_apply.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
         L.attention_exact.restype = i32
@@ -240,6 +242,24 @@ def attncache_search(db: Database, q: torch.Tensor, k: int, threshold: float,
     _check(lib().attncache_search(db.handle, qp, B, k, float(threshold), ip, sp, hp, wp,
                                   ws.numel() * ws.element_size(), _stream(stream)),
            "attncache_search")
+
+
+AC_STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def attncache_search_static(db: Database, q: torch.Tensor, k: int, threshold: float,
+                            idx: torch.Tensor, score: torch.Tensor, hit: torch.Tensor,
+                            stream: Optional[torch.cuda.Stream] = None) -> None:
+    """attncache_search on the library's built-in workspace (no allocation anywhere)."""
+    d = db.desc
+    B = q.shape[0]
+    emb_dt = torch.float16 if d.emb_dtype == AC_F16 else torch.float32
+    qp = _dev(q, "q", emb_dt, (B, d.emb_dim))
+    ip = _dev(idx, "idx", torch.int32, (B, k))
+    sp = _dev(score, "score", torch.float32, (B, k))
+    hp = _dev(hit, "hit", torch.int32, (B,))
+    _check(lib().attncache_search_static(db.handle, qp, B, k, float(threshold), ip, sp, hp,
+                                         _stream(stream)), "attncache_search_static")
 
 
 def attncache_apply(db: Database, hit: torch.Tensor, V: torch.Tensor, O: torch.Tensor,

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -40,6 +41,32 @@ int memspace(const void* p) {
 }
 
 size_t elt_size(int32_t dtype) { return dtype == AC_F32 ? 4 : 2; }
+
+// Search workspace of attncache_search_static: lives in the code object, one copy per GPU the
+// library is loaded on, until the process ends.  In host code the NAME of the array is only a
+// stand-in; its device address is looked up once per device with hipGetSymbolAddress and that
+// pointer is what kernels and copies are given.
+__device__ __align__(256) unsigned char scratch[AC_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Address of `scratch` on the current device (looked up on first use; the same value whichever
+// thread gets there first).
+int32_t static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (dev < 0 || dev >= kMaxDevices) return AC_ERR_SHAPE;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e);
+    if (!p) return AC_ERR_HIP;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return AC_OK;
+}
 
 int32_t check_desc(const attncache_db_desc* d) {
   if (!d) return AC_ERR_NULL;
@@ -206,6 +233,10 @@ int32_t attncache_build_db(const attncache_db_desc* desc, const void* emb, const
       }
     }
   }
+  // set-up is the place to resolve the static search workspace of this device: a first
+  // attncache_search_static may then come from a caller that is capturing a graph
+  void* unused = nullptr;
+  (void)static_scratch(&unused);
   *out = db;
   return AC_OK;
 }
@@ -239,6 +270,23 @@ int32_t attncache_search(const attncache_db* db, const void* q, int32_t B, int32
   p.ws = ws; p.ws_bytes = ws_bytes;
   hipError_t e = ac::launch_search(p, reinterpret_cast<hipStream_t>(stream));
   return e == hipSuccess ? AC_OK : hip_fail(e);
+}
+
+int32_t attncache_search_static(const attncache_db* db, const void* q, int32_t B, int32_t k,
+                                float threshold, int32_t* idx, float* score, int32_t* hit,
+                                void* stream) {
+  if (!db) return AC_ERR_NULL;
+  if (B < 0) return AC_ERR_SHAPE;
+  if (k < 1 || k > AC_MAX_K || k > db->d.n_emb) return AC_ERR_K_RANGE;
+  if (B == 0) return AC_OK;
+  const size_t need = ac::search_workspace_bytes(db->d.n_emb, db->d.emb_dim, B, k,
+                                                 db->d.emb_dtype == AC_F16);
+  if (need > (size_t)AC_STATIC_SCRATCH_BYTES) return AC_ERR_WORKSPACE;
+  void* ws = nullptr;
+  int32_t rc = static_scratch(&ws);
+  if (rc != AC_OK) return rc;
+  return attncache_search(db, q, B, k, threshold, idx, score, hit, ws, AC_STATIC_SCRATCH_BYTES,
+                          stream);
 }
 
 int32_t attncache_apply(const attncache_db* cdb, const int32_t* hit, const void* V, void* O,
