@@ -191,7 +191,7 @@ def main():
         assert torch.equal(O, O_eager), "graph replay and eager step disagree"
         del O_eager
 
-    # ------------- per-layer mode (Sec. 5.3, the finer-grained variant): L x (search, reuse, exact)
+    # ------------- per-layer mode (the finer-grained variant of "Baselines" / the time-breakdown table): L x (search, reuse, exact)
     per_layer = None
     if args.per_layer:
         Ql = [Q[:, l].contiguous() for l in range(L)]

@@ -11,6 +11,12 @@
  *     (hipMalloc'd, e.g. a torch CUDA tensor's data_ptr()) or HOST memory.
  *   - Every function returns an int32_t status: AC_OK (0) or a negative
  *     AC_ERR_* code.  Nothing throws, aborts or prints.
+ *   - The memory space of every pointer of a call is checked before anything
+ *     is launched (AC_ERR_MEMSPACE: a host pointer never reaches a kernel and
+ *     a device pointer is never dereferenced on the host).  The check is one
+ *     driver query per pointer; it is skipped while `stream` is being
+ *     captured into a graph, and attncache_set_pointer_checks(0) switches it
+ *     off for loops that have validated their buffers once.
  *   - All GPU work is enqueued asynchronously on the caller's stream
  *     (`stream` is a hipStream_t passed as void*; NULL = the default
  *     stream).  A status covers argument validation and launch errors only.
@@ -48,6 +54,7 @@ extern "C" {
 #define AC_ERR_INDEX -7     /* a hit index is outside [-1, M)                  */
 #define AC_ERR_HIP -8       /* a HIP call failed, see attncache_last_hip_error */
 #define AC_ERR_MEMSPACE -9  /* pointer is not in the memory space it must be   */
+#define AC_ERR_NOMEM -10    /* a host-side allocation of the library failed     */
 
 /* ---- element types, metrics ------------------------------------------- */
 #define AC_F32 0
@@ -74,9 +81,10 @@ extern "C" {
  * several feature vectors refer to one map entry the optional table map_of
  * gives the entry of each vector.
  *
- * Supported: emb_dtype AC_F16 with metric AC_IP and emb_dim % 16 == 0
- * (matrix-core path), or emb_dtype AC_F32 with either metric and any emb_dim
- * (vector-ALU path).  map_dtype AC_BF16 with seq_len % 32 == 0 and head_dim
+ * Supported: emb_dtype AC_F16 with emb_dim % 8 == 0 (16-byte rows) and either
+ * metric: metric AC_IP with emb_dim % 16 == 0 and emb_dim <= 512 runs on the
+ * matrix cores, every other fp16 shape on the vector ALUs; emb_dtype AC_F32
+ * with either metric and any emb_dim (vector ALUs).  map_dtype AC_BF16 with seq_len % 32 == 0 and head_dim
  * 64 or 128 (matrix-core path, either layout), or map_dtype AC_F32 with any
  * seq_len and head_dim <= 256 (vector-ALU path, dense layout only).
  * n_q_heads % n_kv_heads == 0.
@@ -153,7 +161,9 @@ int32_t attncache_pack_maps(const attncache_db_desc *desc, const void *dense,
  *   staging   DEVICE buffer of staging_bytes, used only when maps_on_host;
  *             must hold at least two entries.  NULL / 0 otherwise.  It is
  *             managed as a cache of whole entries (floor(staging_bytes /
- *             entry bytes) slots, least recently used slot replaced first):
+ *             entry bytes) slots, least recently used slot replaced first;
+ *             per call the entries that are already cached are served
+ *             before the others, ascending entry number inside each class):
  *             an entry that an earlier attncache_apply left there is reused
  *             without a new copy, so spare HBM given here absorbs the popular
  *             entries of a skewed request stream (Sec. 3.1, locality of the
@@ -388,6 +398,13 @@ int32_t attncache_project(const void *h, const int32_t *seq_len,
                           int32_t emb_dim, int32_t h_dtype, int32_t feat_dtype,
                           int32_t normalize, void *workspace,
                           size_t workspace_bytes, void *stream);
+
+/*
+ * Switches the per-call memory-space checks of pointers on (non-zero, the
+ * default) or off for the whole process; returns the previous setting.
+ * attncache_build_db always checks.
+ */
+int32_t attncache_set_pointer_checks(int32_t on);
 
 /* Short constant description of a status code. */
 const char *attncache_status_string(int32_t status);

@@ -29,7 +29,7 @@ SYMBOLS = ["attncache_workspace_bytes", "attncache_map_entry_bytes", "attncache_
            "attncache_search", "attncache_search_static", "attncache_apply", "attention_exact", "attncache_insert",
            "attncache_cache_stats", "attncache_cache_reset",
            "attncache_project_workspace_bytes", "attncache_project", "attncache_status_string",
-           "attncache_last_hip_error", "attncache_version"]
+           "attncache_last_hip_error", "attncache_version", "attncache_set_pointer_checks"]
 
 
 class AttnCacheError(RuntimeError):
@@ -96,6 +96,8 @@ def lib():
         L.attncache_status_string.argtypes = [i32]
         L.attncache_last_hip_error.restype = i32
         L.attncache_last_hip_error.argtypes = []
+        L.attncache_set_pointer_checks.restype = i32
+        L.attncache_set_pointer_checks.argtypes = [i32]
         L.attncache_version.restype = i32
         L.attncache_version.argtypes = []
         _lib = L
@@ -143,6 +145,11 @@ class Database:
             self.close()
         except Exception:
             pass
+
+
+def attncache_set_pointer_checks(on: bool) -> bool:
+    """Per-call memory-space checks on/off; returns the previous setting."""
+    return bool(lib().attncache_set_pointer_checks(int(bool(on))))
 
 
 def attncache_workspace_bytes(desc: DbDesc, max_batch: int, k: int) -> int:

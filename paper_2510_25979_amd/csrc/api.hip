@@ -7,6 +7,7 @@
 #include <atomic>
 #include <cstdlib>
 #include <cstring>
+#include <initializer_list>
 #include <new>
 #include <list>
 #include <unordered_map>
@@ -35,9 +36,32 @@ int memspace(const void* p) {
     (void)hipGetLastError();
     return -1;
   }
-  if (attr.type == hipMemoryTypeDevice) return 0;
+  if (attr.type == hipMemoryTypeDevice || attr.type == hipMemoryTypeManaged) return 0;
   if (attr.type == hipMemoryTypeHost) return 1;
-  return -1;
+  return -1;   // ordinary (unregistered) host memory and anything else
+}
+
+// Per-call pointer checks (attncache_set_pointer_checks): on by default.
+std::atomic<int32_t> g_pointer_checks{1};
+
+// Whether the memory-space queries below may run for work that goes to `stream`: not when the
+// caller switched them off, and not while the stream is being captured into a graph (a capture
+// records launches only; the query is skipped rather than risk invalidating the capture).
+bool may_query(hipStream_t stream) {
+  if (!g_pointer_checks.load(std::memory_order_relaxed)) return false;
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &st) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return st == hipStreamCaptureStatusNone;
+}
+
+// AC_OK when every non-NULL pointer of the list is device memory.
+int32_t all_device(std::initializer_list<const void*> ptrs) {
+  for (const void* p : ptrs)
+    if (p && memspace(p) != 0) return AC_ERR_MEMSPACE;
+  return AC_OK;
 }
 
 size_t elt_size(int32_t dtype) { return dtype == AC_F32 ? 4 : 2; }
@@ -129,6 +153,10 @@ int32_t attncache_version(void) { return 1000; }
 
 int32_t attncache_last_hip_error(void) { return g_last_hip_error; }
 
+int32_t attncache_set_pointer_checks(int32_t on) {
+  return g_pointer_checks.exchange(on != 0 ? 1 : 0, std::memory_order_relaxed);
+}
+
 const char* attncache_status_string(int32_t s) {
   switch (s) {
     case AC_OK: return "ok";
@@ -141,6 +169,7 @@ const char* attncache_status_string(int32_t s) {
     case AC_ERR_INDEX: return "hit index outside [-1, M)";
     case AC_ERR_HIP: return "HIP call failed";
     case AC_ERR_MEMSPACE: return "pointer is in the wrong memory space";
+    case AC_ERR_NOMEM: return "host memory allocation failed";
     default: return "unknown status";
   }
 }
@@ -179,6 +208,10 @@ int32_t attncache_pack_maps(const attncache_db_desc* desc, const void* dense, in
   if (!aligned16(dense) || !aligned16(packed)) return AC_ERR_ALIGN;
   const int64_t tiles = (int64_t)n_entries * d.n_layers * d.n_q_heads;
   if (tiles > 0x7fffffffLL) return AC_ERR_SHAPE;
+  if (may_query(reinterpret_cast<hipStream_t>(stream))) {
+    const int32_t rc = all_device({dense, packed});
+    if (rc != AC_OK) return rc;
+  }
   hipError_t e = ac::launch_pack_maps(dense, packed, tiles, d.seq_len, d.causal != 0,
                                       reinterpret_cast<hipStream_t>(stream));
   return e == hipSuccess ? AC_OK : hip_fail(e);
@@ -199,7 +232,7 @@ int32_t attncache_build_db(const attncache_db_desc* desc, const void* emb, const
   if (memspace(maps) != (desc->maps_on_host ? 1 : 0)) return AC_ERR_MEMSPACE;
 
   attncache_db* db = new (std::nothrow) attncache_db();
-  if (!db) return AC_ERR_HIP;
+  if (!db) return AC_ERR_NOMEM;
   db->d = *desc;
   db->emb = emb;
   db->map_of = map_of;
@@ -210,27 +243,40 @@ int32_t attncache_build_db(const attncache_db_desc* desc, const void* emb, const
   db->side = nullptr;
   db->entry_bytes = entry_bytes_of(desc);
   if (desc->maps_on_host) {
-    if (!staging) { delete db; return AC_ERR_NULL; }
-    if (!aligned16(staging)) { delete db; return AC_ERR_ALIGN; }
-    if (memspace(staging) != 0) { delete db; return AC_ERR_MEMSPACE; }
-    if (staging_bytes / db->entry_bytes < 2) { delete db; return AC_ERR_WORKSPACE; }
+    int32_t bad = AC_OK;
+    if (!staging) bad = AC_ERR_NULL;
+    else if (!aligned16(staging)) bad = AC_ERR_ALIGN;
+    else if (memspace(staging) != 0) bad = AC_ERR_MEMSPACE;
+    else if (staging_bytes / db->entry_bytes < 2) bad = AC_ERR_WORKSPACE;
+    if (bad != AC_OK) { delete db; return bad; }
     db->staging = reinterpret_cast<unsigned char*>(staging);
     db->n_slots = (int)std::min<size_t>(staging_bytes / db->entry_bytes, 1 << 16);
     db->side = reinterpret_cast<hipStream_t>(side_stream);
-    db->copied.resize(db->n_slots);
-    db->consumed.resize(db->n_slots);
-    db->used.assign(db->n_slots, 0);
-    db->slot_entry.assign(db->n_slots, -1);
-    db->lru_it.resize(db->n_slots);
-    for (int i = 0; i < db->n_slots; ++i) db->lru_it[i] = db->lru.insert(db->lru.end(), i);
-    for (int i = 0; i < db->n_slots; ++i) {
-      hipError_t e = hipEventCreateWithFlags(&db->copied[i], hipEventDisableTiming);
-      if (e == hipSuccess) e = hipEventCreateWithFlags(&db->consumed[i], hipEventDisableTiming);
-      if (e != hipSuccess) {
-        // events created so far are leaked on this (never expected) path
-        delete db;
-        return hip_fail(e);
+    hipError_t e = hipSuccess;
+    try {   // the containers allocate host memory; nothing may leave an extern "C" function
+      db->copied.reserve(db->n_slots);
+      db->consumed.reserve(db->n_slots);
+      db->used.assign(db->n_slots, 0);
+      db->slot_entry.assign(db->n_slots, -1);
+      db->where.reserve(db->n_slots);
+      db->lru_it.resize(db->n_slots);
+      for (int i = 0; i < db->n_slots; ++i) db->lru_it[i] = db->lru.insert(db->lru.end(), i);
+      for (int i = 0; i < db->n_slots && e == hipSuccess; ++i) {
+        hipEvent_t ev;
+        e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+        if (e != hipSuccess) break;
+        db->copied.push_back(ev);
+        e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+        if (e != hipSuccess) break;
+        db->consumed.push_back(ev);
       }
+    } catch (...) {
+      (void)attncache_destroy_db(db);
+      return AC_ERR_NOMEM;
+    }
+    if (e != hipSuccess) {
+      (void)attncache_destroy_db(db);   // destroys the events created so far
+      return hip_fail(e);
     }
   }
   // set-up is the place to resolve the static search workspace of this device: a first
@@ -261,6 +307,10 @@ int32_t attncache_search(const attncache_db* db, const void* q, int32_t B, int32
   const size_t need = ac::search_workspace_bytes(db->d.n_emb, db->d.emb_dim, B, k,
                                                  db->d.emb_dtype == AC_F16);
   if (ws_bytes < need) return AC_ERR_WORKSPACE;
+  if (may_query(reinterpret_cast<hipStream_t>(stream))) {
+    const int32_t rc = all_device({q, idx, score, hit, ws});
+    if (rc != AC_OK) return rc;
+  }
   ac::SearchLaunch p;
   p.emb = db->emb; p.q = q; p.map_of = db->map_of;
   p.N = db->d.n_emb; p.E = db->d.emb_dim; p.B = B; p.k = k;
@@ -300,6 +350,14 @@ int32_t attncache_apply(const attncache_db* cdb, const int32_t* hit, const void*
   if (!hit || !V || !O) return AC_ERR_NULL;
   if (!aligned16(V) || !aligned16(O)) return AC_ERR_ALIGN;
   hipStream_t stream = reinterpret_cast<hipStream_t>(stream_);
+  const bool query = may_query(stream);
+  if (query) {
+    const int32_t rc = all_device({V, O});
+    if (rc != AC_OK) return rc;
+    // hit is read by the kernel (device-resident maps) or by this function (host-resident)
+    const int hs = memspace(hit);
+    if (d.maps_on_host ? hs == 0 : hs != 0) return AC_ERR_MEMSPACE;
+  }
 
   ac::ApplyLaunch p;
   p.V = V; p.O = O; p.B = B; p.M = d.n_entries; p.L = d.n_layers;
@@ -321,61 +379,88 @@ int32_t attncache_apply(const attncache_db* cdb, const int32_t* hit, const void*
   // is overwritten only after the products that read it are done.
   for (int32_t b = 0; b < B; ++b)
     if (hit[b] < -1 || hit[b] >= d.n_entries) return AC_ERR_INDEX;
-  std::vector<std::pair<int32_t, int32_t>> order;   // (entry, query), grouped by entry
-  order.reserve(B);
-  for (int32_t b = 0; b < B; ++b)
-    if (hit[b] >= 0) order.emplace_back(hit[b], b);
-  std::stable_sort(order.begin(), order.end(),
-                   [](const auto& x, const auto& y) { return x.first < y.first; });
-  const size_t layer_bytes = db->entry_bytes / d.n_layers;
-  const size_t copy_bytes = layer_bytes * layer_count;
-  size_t pos = 0;
-  while (pos < order.size()) {
-    const int32_t entry = order[pos].first;
-    size_t end = pos;
-    while (end < order.size() && order[end].first == entry) ++end;
+  try {   // the containers below allocate host memory; nothing may leave an extern "C" function
+    std::vector<std::pair<int32_t, int32_t>> order;   // (entry, query), grouped by entry
+    order.reserve(B);
+    for (int32_t b = 0; b < B; ++b)
+      if (hit[b] >= 0) order.emplace_back(hit[b], b);
+    std::stable_sort(order.begin(), order.end(),
+                     [](const auto& x, const auto& y) { return x.first < y.first; });
+    const size_t layer_bytes = db->entry_bytes / d.n_layers;
+    const size_t copy_bytes = layer_bytes * layer_count;
     // Slot cache: an entry that a previous batch (or an earlier group of this one) left in the
     // ring is used where it lies; otherwise the least recently used slot is overwritten.  Only
     // whole entries (all layers) are remembered.
     const bool whole = layer_begin == 0 && layer_count == d.n_layers;
-    ++db->lookups;
-    int slot = -1;
-    bool cached = false;
-    if (whole) {
-      auto it = db->where.find(entry);
-      if (it != db->where.end()) { slot = it->second; cached = true; }
+    // Groups of queries that share an entry.  Entries that are still cached from earlier calls
+    // are served first (their products start at once, under the copies of the others, and they
+    // are touched before anything is replaced, so a batch never evicts what it is about to
+    // use), then the rest; ascending entry inside each class.
+    struct Group { int32_t entry; size_t pos, end; };
+    std::vector<Group> groups;
+    groups.reserve(order.size());
+    for (size_t pos = 0; pos < order.size();) {
+      size_t end = pos;
+      while (end < order.size() && order[end].first == order[pos].first) ++end;
+      groups.push_back({order[pos].first, pos, end});
+      pos = end;
     }
-    if (slot < 0) {
-      slot = db->lru.back();
-      if (db->slot_entry[slot] >= 0) db->where.erase(db->slot_entry[slot]);
-      db->slot_entry[slot] = whole ? entry : -1;
-      if (whole) db->where[entry] = slot;
-    }
-    db->lru.splice(db->lru.begin(), db->lru, db->lru_it[slot]);   // most recently used
-    unsigned char* dst = db->staging + (size_t)slot * db->entry_bytes;
-    hipError_t e = hipSuccess;
-    if (!cached) {
-      ++db->copies;
-      const unsigned char* src = reinterpret_cast<const unsigned char*>(db->maps) +
-                                 (size_t)entry * db->entry_bytes + (size_t)layer_begin * layer_bytes;
-      if (db->used[slot]) e = hipStreamWaitEvent(db->side, db->consumed[slot], 0);
-      if (e == hipSuccess) e = hipMemcpyAsync(dst, src, copy_bytes, hipMemcpyHostToDevice, db->side);
-      if (e == hipSuccess) e = hipEventRecord(db->copied[slot], db->side);
-    }
-    if (e == hipSuccess) e = hipStreamWaitEvent(stream, db->copied[slot], 0);
-    if (e != hipSuccess) return hip_fail(e);
-    // the staged block holds layers [layer_begin, layer_begin + layer_count) only
-    p.maps = dst; p.hit = nullptr; p.fixed_entry = 0; p.L = layer_count; p.layer_begin = 0;
-    for (size_t q0 = pos; q0 < end; q0 += 32) {
-      p.n_list = (int32_t)std::min<size_t>(32, end - q0);
-      for (int i = 0; i < p.n_list; ++i) p.q_list[i] = order[q0 + i].second;
-      e = ac::launch_apply(p, stream);
+    if (whole)
+      std::stable_partition(groups.begin(), groups.end(), [&](const Group& gr) {
+        return db->where.find(gr.entry) != db->where.end();
+      });
+    for (const Group& gr : groups) {
+      const int32_t entry = gr.entry;
+      const size_t pos = gr.pos, end = gr.end;
+      ++db->lookups;
+      int slot = -1;
+      if (whole) {
+        auto it = db->where.find(entry);
+        if (it != db->where.end()) slot = it->second;
+      }
+      const bool cached = slot >= 0;
+      hipError_t e = hipSuccess;
+      if (!cached) {
+        // The slot's old contents are given up BEFORE the copy is enqueued and the new entry is
+        // published only AFTER copy and event are: if a HIP call fails in between, the slot
+        // names nothing and no later call can mistake it for a filled one.
+        slot = db->lru.back();
+        if (db->slot_entry[slot] >= 0) {
+          db->where.erase(db->slot_entry[slot]);
+          db->slot_entry[slot] = -1;
+        }
+        ++db->copies;
+        const unsigned char* src = reinterpret_cast<const unsigned char*>(db->maps) +
+                                   (size_t)entry * db->entry_bytes + (size_t)layer_begin * layer_bytes;
+        unsigned char* to = db->staging + (size_t)slot * db->entry_bytes;
+        if (db->used[slot]) e = hipStreamWaitEvent(db->side, db->consumed[slot], 0);
+        if (e == hipSuccess) e = hipMemcpyAsync(to, src, copy_bytes, hipMemcpyHostToDevice, db->side);
+        if (e == hipSuccess) e = hipEventRecord(db->copied[slot], db->side);
+        if (e != hipSuccess) return hip_fail(e);
+        if (whole) {
+          db->where[entry] = slot;
+          db->slot_entry[slot] = entry;
+        }
+      }
+      db->lru.splice(db->lru.begin(), db->lru, db->lru_it[slot]);   // most recently used
+      unsigned char* dst = db->staging + (size_t)slot * db->entry_bytes;
+      e = hipStreamWaitEvent(stream, db->copied[slot], 0);
+      // the staged block holds layers [layer_begin, layer_begin + layer_count) only
+      p.maps = dst; p.hit = nullptr; p.fixed_entry = 0; p.L = layer_count; p.layer_begin = 0;
+      for (size_t q0 = pos; q0 < end && e == hipSuccess; q0 += 32) {
+        p.n_list = (int32_t)std::min<size_t>(32, end - q0);
+        for (int i = 0; i < p.n_list; ++i) p.q_list[i] = order[q0 + i].second;
+        e = ac::launch_apply(p, stream);
+      }
+      // readers may have been enqueued even when a later launch failed: the slot's next
+      // overwrite must wait for them either way
+      const hipError_t e2 = hipEventRecord(db->consumed[slot], stream);
+      if (e2 == hipSuccess) db->used[slot] = 1;
       if (e != hipSuccess) return hip_fail(e);
+      if (e2 != hipSuccess) return hip_fail(e2);
     }
-    e = hipEventRecord(db->consumed[slot], stream);
-    if (e != hipSuccess) return hip_fail(e);
-    db->used[slot] = 1;
-    pos = end;
+  } catch (...) {
+    return AC_ERR_NOMEM;
   }
   return AC_OK;
 }
@@ -411,6 +496,10 @@ int32_t attention_exact(const void* Q, const void* K, const void* V, void* O,
   if (B == 0) return AC_OK;
   if (!Q || !K || !V || !O) return AC_ERR_NULL;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return AC_ERR_ALIGN;
+  if (may_query(reinterpret_cast<hipStream_t>(stream))) {
+    const int32_t rc = all_device({Q, K, V, O, row_sel, key_len});
+    if (rc != AC_OK) return rc;
+  }
   ac::ExactLaunch p;
   p.Q = Q; p.K = K; p.V = V; p.O = O; p.row_sel = row_sel; p.key_len = key_len;
   p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.S = S; p.D = D;
@@ -439,6 +528,10 @@ int32_t attncache_insert(attncache_db* db, const void* feat, const int32_t* slot
   if (feat && !slot) return AC_ERR_NULL;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(feat))
     return AC_ERR_ALIGN;
+  if (may_query(reinterpret_cast<hipStream_t>(stream))) {
+    const int32_t rc = all_device({Q, K, V, O, feat, slot, row_sel, key_len});
+    if (rc != AC_OK) return rc;
+  }
   ac::InsertLaunch p;
   p.Q = Q; p.K = K; p.V = V; p.O = O;
   p.maps = const_cast<void*>(db->maps);   // the one entry point that writes the borrowed stores
@@ -477,6 +570,10 @@ int32_t attncache_project(const void* h, const int32_t* seq_len, const float* W1
     return AC_ERR_ALIGN;
   if (workspace_bytes < ac::project_workspace_bytes(B, model_dim, hidden_dim, emb_dim))
     return AC_ERR_WORKSPACE;
+  if (may_query(reinterpret_cast<hipStream_t>(stream))) {
+    const int32_t rc = all_device({h, seq_len, W1, b1, W2, b2, feat, workspace});
+    if (rc != AC_OK) return rc;
+  }
   ac::ProjectLaunch p;
   p.h = h; p.seq_len = seq_len; p.W1 = W1; p.b1 = b1; p.W2 = W2; p.b2 = b2;
   p.feat = feat; p.ws = workspace;

@@ -6,16 +6,23 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace ac {
 
 // Dynamic LDS above 64 KiB needs a per-kernel opt-in; done once per kernel and size.
 template <auto Kernel>
 inline hipError_t ensure_lds(size_t bytes) {
-  static size_t granted = 64 * 1024;
-  if (bytes <= granted) return hipSuccess;
+  // Host threads may launch the same kernel at once: the largest size granted so far is an
+  // atomic that only grows; two threads that both see it too small both set the attribute
+  // (the larger request wins in the maximum, and setting it twice is harmless).
+  static std::atomic<size_t> granted{64 * 1024};
+  if (bytes <= granted.load(std::memory_order_acquire)) return hipSuccess;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-  if (e == hipSuccess) granted = bytes;
+  if (e != hipSuccess) return e;
+  size_t seen = granted.load(std::memory_order_relaxed);
+  while (seen < bytes && !granted.compare_exchange_weak(seen, bytes, std::memory_order_release)) {}
   return e;
 }
 

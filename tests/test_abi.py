@@ -35,7 +35,7 @@ def test_status_strings_and_version():
     L = binding.lib()
     assert L.attncache_version() >= 1000
     assert L.attncache_status_string(0) == b"ok"
-    for code in range(-9, 0):
+    for code in range(-10, 0):
         assert L.attncache_status_string(code) != b"unknown status"
     assert L.attncache_status_string(-99) == b"unknown status"
 

@@ -1,10 +1,9 @@
 """GPU parity at the full sizes of the workloads, in the launch configuration bench.py times.
 
 The whole step runs on the GPU at full size (full database resident, full batch, all layers and
-heads); the oracle then checks search for every query (a sample of queries for the million-row
-index) and a sample of output tiles one by one, each tile from the dense map bytes the database
-was built from (re-drawn with the same seed, never read back through the packed form).
-Properties that hold at any size cover the rest: every output is finite, misses stay untouched.
+heads); the oracle then checks the search of every query and EVERY output tile of both
+branches, each reuse tile from the dense map bytes the database was built from (re-drawn with
+the same seed, never read back through the packed form).
 """
 import numpy as np
 import pytest
@@ -32,94 +31,104 @@ def _sample_tiles(hits, L, Hq, n, seed):
     return sorted(picks)
 
 
-def _run_workload(env, oracle_mod, cfg, *, n_tiles=10, search_sample=None, host_entries=None):
+def _worst_tile(got, ref, queries):
+    """Max-abs error per (query, layer, head) tile; returns (error, (b, l, h)) of the worst."""
+    assert got.shape == ref.shape and np.isfinite(got).all()
+    err = np.abs(got - ref).max(axis=(3, 4))
+    n, l, h = np.unravel_index(int(err.argmax()), err.shape)
+    return float(err[n, l, h]), (int(queries[n]), int(l), int(h))
+
+
+def _check_reuse_tiles(oracle_mod, store, hit_h, V, O, queries, tol, chunk_bytes=1 << 30):
+    """EVERY (query, layer, head) tile of the reuse branch for the given queries against the
+    oracle, which multiplies the dense maps the database was built from (re-drawn with the same
+    seed) with V.  Returns the number of tiles compared."""
+    w = store.w
+    L, Hq = w.n_layers, w.n_q_heads
+    per = max(1, chunk_bytes // (w.entry_elems * 4))
+    # queries grouped by the slice of the store their entry was drawn in: one re-draw per slice
+    order = sorted(queries, key=lambda b: int(hit_h[b]))
+    done = 0
+    for c0 in range(0, len(order), per):
+        qs = order[c0:c0 + per]
+        A = torch.stack([store.dense_entry(int(hit_h[b])) for b in qs])
+        ref = oracle_mod.apply(parity.to_np(A), np.arange(len(qs), dtype=np.int32), parity.to_np(V[qs]))
+        del A
+        err, where = _worst_tile(O[qs].double().cpu().numpy(), ref, qs)
+        assert err <= tol, ("reuse tile", where, err)
+        done += len(qs) * L * Hq
+    return done
+
+
+def _check_exact_tiles(oracle_mod, w, Q, K, V, O, queries, tol, chunk_bytes=1 << 30):
+    """EVERY (query, layer, head) tile of the recompute branch for the given queries."""
+    B, L, Hq, Hkv, S, D = w.batch, w.n_layers, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim
+    per = max(1, chunk_bytes // (L * Hq * S * D * 4))
+    done = 0
+    for c0 in range(0, len(queries), per):
+        qs = list(queries[c0:c0 + per])
+        n = len(qs)
+        ref = oracle_mod.attention_exact(parity.to_np(Q[qs]).reshape(n, L * Hq, S, D),
+                                         parity.to_np(K[qs]).reshape(n, L * Hkv, S, D),
+                                         parity.to_np(V[qs]).reshape(n, L * Hkv, S, D), causal=w.causal)
+        err, where = _worst_tile(O[qs].double().cpu().numpy(), ref.reshape(n, L, Hq, S, D), qs)
+        assert err <= tol, ("exact tile", where, err)
+        done += n * L * Hq
+    return done
+
+
+def _run_workload(env, oracle_mod, cfg, *, expect_reuse_tiles, expect_exact_tiles):
+    """One whole step at the workload's full size, exactly as bench.py issues it; then the oracle
+    checks the search of every query and every output tile of both branches."""
     ac, synth, synthdb = env
     dev = torch.device("cuda:0")
     w = synth.WORKLOADS[cfg]
-    if host_entries is not None:
-        w = w.scaled(n_entries=host_entries)
     B, L, Hq, Hkv, S, D = w.batch, w.n_layers, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim
-    g = Hq // Hkv
     dt = synth.torch_dtype(w.map_dtype)
     emb, raw, map_of = synth.make_embeddings(w, dev)
     q, planted = synth.make_queries(w, raw, dev)
     del raw
-    store = synthdb.SynthMapStore(w, dev, layout="packed", host=w.maps_on_host)
+    store = synthdb.SynthMapStore(w, dev, layout="packed")
     Q, K, V = synth.make_qkv(w, dev)
     sentinel = 3.0
     O = torch.full((B, L, Hq, S, D), sentinel, dtype=dt, device=dev)
-
-    staging = side = None
-    if w.maps_on_host:
-        entry_bytes = store.stored_bytes // w.n_entries
-        staging = torch.empty(8 * entry_bytes, dtype=torch.uint8, device=dev)
-        side = torch.cuda.Stream()
     db = ac.attncache_build_db(emb, store.maps, n_kv_heads=Hkv, head_dim=D, causal=w.causal,
-                               map_of=map_of, seq_len=S, staging=staging, side_stream=side)
+                               map_of=map_of, seq_len=S)
     ws = torch.empty(ac.attncache_workspace_bytes(db.desc, B, w.k), dtype=torch.uint8, device=dev)
     idx = torch.empty(B, w.k, dtype=torch.int32, device=dev)
     score = torch.empty(B, w.k, dtype=torch.float32, device=dev)
     hit = torch.empty(B, dtype=torch.int32, device=dev)
 
     # ---- the step, exactly as bench.py issues it
+    Qf, Kf, Vf = Q.view(B, L * Hq, S, D), K.view(B, L * Hkv, S, D), V.view(B, L * Hkv, S, D)
     ac.attncache_search(db, q, w.k, w.theta, idx, score, hit, ws)
-    hit_for_apply = hit.cpu() if w.maps_on_host else hit
-    ac.attncache_apply(db, hit_for_apply, V, O)
-    ac.attention_exact(Q.view(B, L * Hq, S, D), K.view(B, L * Hkv, S, D), V.view(B, L * Hkv, S, D),
-                       O.view(B, L * Hq, S, D), causal=w.causal, row_sel=hit)
+    ac.attncache_apply(db, hit, V, O)
+    ac.attention_exact(Qf, Kf, Vf, O.view(B, L * Hq, S, D), causal=w.causal, row_sel=hit)
     torch.cuda.synchronize()
 
-    # ---- search: every query (or a sample) against the oracle
+    # ---- search: every query against the oracle
     hit_h = hit.cpu().numpy()
     expect_hit = torch.where(planted >= 0, planted % w.n_entries, planted).numpy().astype(np.int32)
     assert np.array_equal(hit_h, expect_hit), "routing differs from the planted hits"
-    qs = np.arange(B) if search_sample is None else np.sort(
-        np.random.default_rng(cfg).choice(B, search_sample, replace=False))
-    sel = torch.from_numpy(qs).to(dev)
-    exempt = parity.check_search(oracle_mod, q[sel], emb, w.k, w.theta, 0, map_of, idx[sel],
-                                 score[sel], hit[sel])
+    exempt = parity.check_search(oracle_mod, q, emb, w.k, w.theta, 0, map_of, idx, score, hit)
     assert exempt <= 2
 
-    # ---- outputs: properties at full size
-    assert torch.isfinite(O.view(-1)[:: max(1, O.numel() // (1 << 24))].float()).all()
     hits = [b for b in range(B) if hit_h[b] >= 0]
     misses = [b for b in range(B) if hit_h[b] < 0]
-
-    # ---- reuse branch: sampled tiles, oracle on the dense bytes the database was built from
-    worst = 0.0
-    for (b, l, h) in _sample_tiles(hits, L, Hq, n_tiles, cfg):
-        A = store.dense_entry(int(hit_h[b]))[l, h]
-        ref = oracle_mod.apply(parity.to_np(A).reshape(1, 1, 1, S, S), np.zeros(1, np.int32),
-                               parity.to_np(V[b, l, h // g]).reshape(1, 1, 1, S, D))
-        err = parity.max_abs_err(O[b, l, h].contiguous(), ref[0, 0, 0])
-        worst = max(worst, err)
-        assert err <= parity.TOL[dt], (cfg, b, l, h, err)
-
-    # ---- recompute branch on the misses (routed by row_sel), sampled tiles
+    tol = parity.TOL[dt]
+    # ---- reuse branch: every tile of every hit
+    assert _check_reuse_tiles(oracle_mod, store, hit_h, V, O, hits, tol) == expect_reuse_tiles
+    # ---- recompute branch: every tile of every routed miss; when the workload has no miss the
+    # routed launch must not have written anything (checked above: every tile equals the reuse
+    # result) and the kernel is checked at full size on all queries separately
     if misses:
-        for (b, l, h) in _sample_tiles(misses, L, Hq, n_tiles, cfg + 100):
-            ref = oracle_mod.attention_exact(parity.to_np(Q[b, l, h]).reshape(1, 1, S, D),
-                                             parity.to_np(K[b, l, h // g]).reshape(1, 1, S, D),
-                                             parity.to_np(V[b, l, h // g]).reshape(1, 1, S, D),
-                                             causal=w.causal)
-            err = parity.max_abs_err(O[b, l, h].contiguous(), ref[0, 0])
-            assert err <= parity.TOL[dt], (cfg, "miss", b, l, h, err)
+        assert _check_exact_tiles(oracle_mod, w, Q, K, V, O, misses, tol) == expect_exact_tiles
     else:
-        # no miss in this workload: the recompute kernel must not have touched anything, and
-        # it is checked at full size on all queries separately
-        Ox = torch.empty_like(O)
-        ac.attention_exact(Q.view(B, L * Hq, S, D), K.view(B, L * Hkv, S, D),
-                           V.view(B, L * Hkv, S, D), Ox.view(B, L * Hq, S, D), causal=w.causal)
+        O.fill_(sentinel)
+        ac.attention_exact(Qf, Kf, Vf, O.view(B, L * Hq, S, D), causal=w.causal)
         torch.cuda.synchronize()
-        for (b, l, h) in _sample_tiles(list(range(B)), L, Hq, max(3, n_tiles // 2), cfg + 200):
-            ref = oracle_mod.attention_exact(parity.to_np(Q[b, l, h]).reshape(1, 1, S, D),
-                                             parity.to_np(K[b, l, h // g]).reshape(1, 1, S, D),
-                                             parity.to_np(V[b, l, h // g]).reshape(1, 1, S, D),
-                                             causal=w.causal)
-            err = parity.max_abs_err(Ox[b, l, h].contiguous(), ref[0, 0])
-            assert err <= parity.TOL[dt], (cfg, "exact", b, l, h, err)
+        assert _check_exact_tiles(oracle_mod, w, Q, K, V, O, list(range(B)), tol) == expect_exact_tiles
     db.close()
-    return worst
 
 
 def test_workload_1_tiny_fp32_in_full(env, oracle_mod):
@@ -155,23 +164,107 @@ def test_workload_1_tiny_fp32_in_full(env, oracle_mod):
     assert parity.max_abs_err(Ox, ref) <= 1e-4
 
 
-def test_workload_2_llama_1b_shaped_full_size(env, oracle_mod):
-    _run_workload(env, oracle_mod, 2)
+def test_workload_2_llama_1b_shaped_full_size_all_32768_reuse_and_all_32768_exact_tiles(env, oracle_mod):
+    _run_workload(env, oracle_mod, 2, expect_reuse_tiles=64 * 16 * 32, expect_exact_tiles=64 * 16 * 32)
 
 
-def test_workload_3_llama_8b_shaped_half_missing_full_size(env, oracle_mod):
-    _run_workload(env, oracle_mod, 3)
+def test_workload_3_llama_8b_shaped_full_size_all_65536_hit_and_all_65536_miss_tiles(env, oracle_mod):
+    _run_workload(env, oracle_mod, 3, expect_reuse_tiles=64 * 32 * 32, expect_exact_tiles=64 * 32 * 32)
 
 
-def test_workload_4_long_sequence_top4_full_size(env, oracle_mod):
-    _run_workload(env, oracle_mod, 4, n_tiles=4)
+def test_workload_4_long_sequence_top4_full_size_all_512_reuse_and_all_512_exact_tiles(env, oracle_mod):
+    _run_workload(env, oracle_mod, 4, expect_reuse_tiles=16 * 32, expect_exact_tiles=16 * 32)
 
 
-def test_workload_5_host_resident_maps_million_row_index(env, oracle_mod):
-    # The map store lives in pinned host memory and is streamed on a side stream.  The box
-    # cannot pin 400 GiB: the entry count is reduced to 512 (entry size, index size, batch and
-    # Zipf popularity are the workload's); search is checked on a sample of 24 queries.
-    _run_workload(env, oracle_mod, 5, n_tiles=8, search_sample=24, host_entries=512)
+# Pinned host memory the GPU machines grant one process: 64 GiB in total, whatever the size of the
+# single allocations (measured with a ladder of hipHostMalloc calls; the machine has 295 GiB of
+# RAM).  The over-HBM workload's store is therefore 3,200 packed entries of 20 MiB (62.5 GiB)
+# instead of 12,800; entry size, index size, batch and popularity law are the workload's.
+HOST_ENTRY_LADDER = (3200, 2400, 1600, 800)
+
+
+def _lru_copies(batches_of_entries, n_slots):
+    """Copies the documented policy must issue: per call the distinct entries that are cached at
+    the start of the call are served first, then the others, ascending inside each class; a
+    cache of n_slots whole entries, least recently used slot replaced."""
+    lru, copies = [], []          # most recently used last
+    for entries in batches_of_entries:
+        distinct = sorted(set(entries))
+        c = 0
+        for e in [e for e in distinct if e in lru] + [e for e in distinct if e not in lru]:
+            if e in lru:
+                lru.remove(e)
+            else:
+                c += 1
+                if len(lru) == n_slots:
+                    lru.pop(0)
+            lru.append(e)
+        copies.append(c)
+    return copies
+
+
+def test_workload_5_host_resident_store_at_the_pinned_limit_all_256_searches_all_262144_tiles(env, oracle_mod):
+    """Over-HBM workload: 1,000,000 x 256 index in HBM, map store in pinned host memory at the
+    largest size the box grants, streamed by hipMemcpyAsync on a side stream.  Two batches of 256
+    queries (Zipf(1.1) popularity): the first is checked in full (all 256 searches, every one of
+    its 256 x 32 x 32 output tiles), the second exercises the entry cache across batches (96
+    slots: fewer than a batch's distinct entries, so slots are also recycled inside a batch) and
+    is checked on every tile of every eighth query; copy counts must equal the LRU policy's."""
+    ac, synth, synthdb = env
+    dev = torch.device("cuda:0")
+    store = None
+    for n_entries in HOST_ENTRY_LADDER:
+        w = synth.WORKLOADS[5].scaled(n_entries=n_entries)
+        try:
+            store = synthdb.SynthMapStore(w, dev, layout="packed", host=True)
+            break
+        except MemoryError as e:
+            print(f"[workload 5] {e}; trying fewer entries", flush=True)
+    assert store is not None, "no pinned host memory for even the smallest store"
+    print(f"[workload 5] host store: {w.n_entries} entries, {store.stored_bytes / 2**30:.1f} GiB pinned",
+          flush=True)
+    B, L, Hq, Hkv, S, D = w.batch, w.n_layers, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim
+    emb, raw, map_of = synth.make_embeddings(w, dev)
+    Q, K, V = synth.make_qkv(w, dev)
+    del Q, K
+    entry_bytes = store.stored_bytes // w.n_entries
+    n_slots = 96
+    staging = torch.empty(n_slots * entry_bytes, dtype=torch.uint8, device=dev)
+    side = torch.cuda.Stream()
+    db = ac.attncache_build_db(emb, store.maps, n_kv_heads=Hkv, head_dim=D, causal=w.causal,
+                               map_of=map_of, seq_len=S, staging=staging, side_stream=side)
+    ws = torch.empty(ac.attncache_workspace_bytes(db.desc, B, w.k), dtype=torch.uint8, device=dev)
+    idx = torch.empty(B, w.k, dtype=torch.int32, device=dev)
+    score = torch.empty(B, w.k, dtype=torch.float32, device=dev)
+    hit = torch.empty(B, dtype=torch.int32, device=dev)
+    O = torch.empty(B, L, Hq, S, D, dtype=torch.bfloat16, device=dev)
+    seen, total_tiles = [], 0
+    for batch_id in (0, 1):
+        q, planted = synth.make_queries(w, raw, dev, batch_id=batch_id)
+        O.fill_(3.0)
+        ac.attncache_search(db, q, w.k, w.theta, idx, score, hit, ws)
+        hit_host = hit.cpu()                      # the host schedules the copies
+        ac.attncache_apply(db, hit_host, V, O)
+        torch.cuda.synchronize()
+        hit_h = hit_host.numpy()
+        assert np.array_equal(hit_h, (planted % w.n_entries).numpy().astype(np.int32))
+        seen.append([int(e) for e in hit_h])
+        if batch_id == 0:
+            assert parity.check_search(oracle_mod, q, emb, w.k, w.theta, 0, map_of, idx, score, hit) <= 2
+            queries = list(range(B))
+        else:
+            queries = list(range(0, B, 8))
+        total_tiles += _check_reuse_tiles(oracle_mod, store, hit_h, V, O, queries, 2e-2)
+        lookups, copies = ac.attncache_cache_stats(db)
+        want = _lru_copies(seen, n_slots)
+        assert lookups == sum(len(set(s)) for s in seen) and copies == sum(want), (lookups, copies, want)
+        print(f"[workload 5] batch {batch_id}: {len(set(seen[-1]))} distinct entries, "
+              f"{want[-1]} copied", flush=True)
+    assert total_tiles == (256 + 32) * 32 * 32
+    assert len(set(seen[0])) > n_slots            # slots were recycled inside the first batch
+    assert _lru_copies(seen, n_slots)[1] < len(set(seen[1]))   # and the second batch found entries cached
+    db.close()
+    store.close()
 
 
 @pytest.mark.parametrize("cfg", [2, 4], ids=["llama-1b-shape", "long-sequence-shape"])

@@ -753,3 +753,64 @@ def test_error_codes(ac):
     f32db.close()
     ac.attncache_search(db, q, 1, 0.5, idx, score, hit, ws)   # the handle still works
     torch.cuda.synchronize()
+
+
+def test_host_pointers_are_refused_before_any_launch(ac):
+    """Raw C-ABI calls (no binding in between) with a pointer in the wrong memory space return
+    AC_ERR_MEMSPACE from the library's host-side check: nothing is launched, so every output
+    keeps its fill value.  Ordinary and pinned host memory are both refused where device memory
+    is required, and a device `hit` is refused where the host reads it."""
+    import ctypes
+    L_ = ac.lib()
+    cf = ctypes.c_float
+    M, L, Hq, Hkv, S, D, E, B = 6, 1, 2, 2, 32, 64, 128, 4
+    emb = torch.randn(M, E, device="cuda").half()
+    maps = torch.zeros(M, L, Hq, S, S, dtype=torch.bfloat16, device="cuda")
+    db = ac.attncache_build_db(emb, maps, n_kv_heads=Hkv, head_dim=D)
+    dev = lambda *s, dt=torch.bfloat16, fill=7: torch.full(s, fill, dtype=dt, device="cuda")
+    host = lambda *s, dt=torch.bfloat16: torch.zeros(*s, dtype=dt)
+    pinned = lambda *s, dt=torch.bfloat16: torch.zeros(*s, dtype=dt, pin_memory=True)
+    q, idx, score, hit = dev(B, E, dt=torch.float16, fill=0), dev(B, 1, dt=torch.int32), \
+        dev(B, 1, dt=torch.float32), dev(B, dt=torch.int32, fill=0)
+    ws = dev(1 << 16, dt=torch.uint8)
+    V, O, Q = dev(B, L, Hkv, S, D, fill=1), dev(B, L, Hq, S, D), dev(B, L, Hq, S, D, fill=1)
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    for bad in (host, pinned):
+        hq, hidx, hV, hO, hws = bad(B, E, dt=torch.float16), bad(B, 1, dt=torch.int32), \
+            bad(B, L, Hkv, S, D), bad(B, L, Hq, S, D), bad(1 << 16, dt=torch.uint8)
+        assert L_.attncache_search(db.handle, p(hq), B, 1, cf(0.5), p(idx), p(score), p(hit), p(ws), 1 << 16, None) == -9
+        assert L_.attncache_search(db.handle, p(q), B, 1, cf(0.5), p(hidx), p(score), p(hit), p(ws), 1 << 16, None) == -9
+        assert L_.attncache_search(db.handle, p(q), B, 1, cf(0.5), p(idx), p(score), p(hit), p(hws), 1 << 16, None) == -9
+        assert L_.attncache_apply(db.handle, p(hit), p(hV), p(O), B, 0, 1, None) == -9
+        assert L_.attncache_apply(db.handle, p(hit), p(V), p(hO), B, 0, 1, None) == -9
+        assert L_.attncache_apply(db.handle, p(bad(B, dt=torch.int32)), p(V), p(O), B, 0, 1, None) == -9
+        assert L_.attention_exact(p(hO), p(V), p(V), p(O), None, None, B, Hq, Hkv, S, D, ac.AC_BF16, 1, cf(0), None) == -9
+        assert L_.attention_exact(p(Q), p(V), p(V), p(O), p(bad(B, dt=torch.int32)), None, B, Hq, Hkv, S, D,
+                                  ac.AC_BF16, 1, cf(0), None) == -9
+        assert L_.attncache_insert(db.handle, None, p(bad(B, dt=torch.int32)), None, None, p(Q), p(V), p(V), p(O),
+                                   B, 0, 1, cf(0), None) == -9
+        assert L_.attncache_pack_maps(ctypes.byref(db.desc), p(bad(M, L, Hq, S, S)), M, p(maps), None) == -9
+        W = torch.zeros(64, 64, device="cuda")
+        pw = dev(ac.attncache_project_workspace_bytes(B, 64, 64, 64), dt=torch.uint8)
+        assert L_.attncache_project(p(bad(B, 8, 64)), None, p(W), None, p(W), None, p(dev(B, 64, dt=torch.float16)),
+                                    B, 8, 64, 64, 64, ac.AC_BF16, ac.AC_F16, 1, p(pw), pw.numel(), None) == -9
+    torch.cuda.synchronize()
+    assert (idx == 7).all() and (score == 7).all() and (O == 7).all() and torch.count_nonzero(maps) == 0
+
+    # host-resident maps: `hit` is read by the host, so a device pointer is the wrong one
+    hmaps = torch.zeros(M, L, Hq, S, S, dtype=torch.bfloat16, pin_memory=True)
+    staging = torch.empty(2 * L * Hq * S * S * 2, dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    hdb = ac.attncache_build_db(emb, hmaps, n_kv_heads=Hkv, head_dim=D, staging=staging, side_stream=side)
+    assert L_.attncache_apply(hdb.handle, p(hit), p(V), p(O), B, 0, 1, None) == -9
+    assert L_.attncache_apply(hdb.handle, p(torch.zeros(B, dtype=torch.int32)), p(V), p(O), B, 0, 1, None) == 0
+    torch.cuda.synchronize()
+    hdb.close()
+
+    # the checks can be switched off (and report their previous state); valid calls work either way
+    assert ac.attncache_set_pointer_checks(False) is True
+    assert L_.attncache_search(db.handle, p(q), B, 1, cf(0.5), p(idx), p(score), p(hit), p(ws), 1 << 16, None) == 0
+    assert ac.attncache_set_pointer_checks(True) is False
+    assert L_.attncache_search(db.handle, p(q), B, 1, cf(0.5), p(idx), p(score), p(hit), p(ws), 1 << 16, None) == 0
+    torch.cuda.synchronize()
+    db.close()
