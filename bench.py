@@ -3,16 +3,25 @@
 
 One "step" = one pass of the whole path over one batch of synthetic queries:
 similarity search -> hit/miss routing -> map reuse (O = A_cached . V over all
-layers and heads of the hits) -> exact attention for the misses.  The default
+layers and heads of the hits) -> exact attention for the misses.  The headline
 workload is the Llama-3.2-1B-shaped one (16 layers x 32 heads, head_dim 64,
 S = 128, bf16; 10,000-entry database resident in HBM; batch 64, all planted).
 
-Prints ONE JSON line.  `value` is tokens/s of the whole step with every input
-already resident in HBM; the K timed steps are replays of one captured HIP
-graph of the step (`--launch eager` issues the library calls one by one
-instead; that figure is reported beside it either way).  Beside it: the reuse-only and exact-only rates and
-their ratio, search QPS, the roofline record of the dominant kernel (map
-reuse, HBM-bound) and the CPU oracle timed on a bounded sample.
+Prints ONE JSON line.  `value` is tokens/s of the whole step of the headline
+workload with every input already resident in HBM; the K timed steps are
+replays of one captured HIP graph of the step (`--launch eager` issues the
+library calls one by one instead; that figure is reported beside it either
+way).  Beside it: the reuse-only and exact-only rates and their ratio, search
+QPS, the roofline record of the dominant kernel (map reuse, HBM-bound) and the
+CPU oracle timed on a bounded sample.
+
+The object `workloads` carries the same measurements for the other workloads
+(the 8B-shaped one with half the batch missing, the long-sequence layer, the
+search alone on the million-row index at 64..1024 queries, the host-resident
+store streamed over the host link) and for the steps around the path (database
+building on the device, feature projector, per-layer mode), each with the
+roofline record of its own dominant kernel and an oracle timing on a stated
+sample (scaled to the whole batch where the sample is smaller).
 """
 import argparse
 import json
@@ -25,108 +34,119 @@ import torch
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM bytes per reuse launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (scaled by a plain copy of known size; the runs are summarised under profiles/), as a
-# multiple of the algorithmic bytes of the same launch.
-MEASURED_TRAFFIC_RATIO = {("llama-3.2-1b-shaped", "packed"): 1.0001,
-                          ("llama-3.2-1b-shaped", "dense"): 1.075,
-                          ("long-sequence-layer", "packed"): 1.0064}
-MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
+HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 / fp16 matrix rate
+HOST_LINK_PEAK_GBS = 64.0       # PCIe Gen5 x16, one direction, theoretical
 
 
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def apply_algorithmic_bytes(w, n_hits):
-    """Bytes one reuse launch must move: per (query, layer, head) the causal part of the map at
-    the kernel's 32-row granularity, S(S+32) bf16 elements / 2 ... i.e. S(S+32) bytes; V once per
-    head group; O once."""
+# --------------------------------------------------------------------- algorithmic work
+
+def apply_bytes(w, n_hits, dense_equivalent=False):
+    """Bytes one reuse launch must move: per (query, layer, head) the map (causal: the part
+    at and below the diagonal at the kernel's 32-column granularity, S(S+32)/2 elements;
+    dense-equivalent: all S^2), V once per group of heads that share it, O once."""
     S, D, g = w.seq_len, w.head_dim, w.n_q_heads // w.n_kv_heads
     esz = 2 if w.map_dtype == "bf16" else 4
-    a = (S * (S + 32) // 2 if w.causal else S * S) * esz
-    per_tile = a + S * D * esz // g + S * D * esz
-    return per_tile * n_hits * w.n_layers * w.n_q_heads
+    a = (S * (S + 32) // 2 if (w.causal and not dense_equivalent) else S * S) * esz
+    return (a + S * D * esz // g + S * D * esz) * n_hits * w.n_layers * w.n_q_heads
 
 
-def exact_algorithmic_bytes(w, n_items):
+def exact_bytes(w, n_items):
     S, D, g = w.seq_len, w.head_dim, w.n_q_heads // w.n_kv_heads
     esz = 2 if w.map_dtype == "bf16" else 4
-    per_head = S * D * esz * (2 + 2 / g)
-    return per_head * n_items * w.n_layers * w.n_q_heads
+    return S * D * esz * (2 + 2 / g) * n_items * w.n_layers * w.n_q_heads
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", type=int, default=2, help="workload number 1..4 (default 2)")
-    ap.add_argument("--entries", type=int, default=0, help="override the number of map entries")
-    ap.add_argument("--layout", choices=["packed", "dense"], default="packed",
-                    help="storage layout of the map database (default: packed)")
-    ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
-                    help="how the K timed steps are issued: replays of one captured HIP graph of "
-                         "the step (default), or one library call after the other")
-    ap.add_argument("--per-layer", action="store_true",
-                    help="also time the per-layer mode (every layer runs its own search, reuse and "
-                         "recompute launch; the whole chain is one HIP graph) and report it as "
-                         "`per_layer_mode`")
-    ap.add_argument("--projector", action="store_true",
-                    help="also time the feature projector in front of the search (hidden states "
-                         "[B][S][Hq*D] bf16, hidden width a quarter of that, synthetic weights) and "
-                         "report it as `projector`; it is not part of the timed step")
-    ap.add_argument("--index-probe", action="store_true",
-                    help="also time attncache_search alone on the over-HBM workload's index (1,000,000 x "
-                         "256 fp16 feature vectors, 256 and 64 queries) and report it as "
-                         "`large_index_search`; not part of the timed step")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="also launch one plain 1 GiB device copy (a kernel of known HBM traffic "
-                         "against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
-              "use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
-        sys.exit(3)
+def exact_flops(w, n_items, dense_equivalent=False):
+    """Two products of 2 S^2 D flops each; causal-useful: the S(S+1)/2 visible scores only."""
+    S, D = w.seq_len, w.head_dim
+    scores = S * S if (dense_equivalent or not w.causal) else S * (S + 1) // 2
+    return 4.0 * scores * D * n_items * w.n_layers * w.n_q_heads
 
-    from paper_2510_25979_amd import binding as ac
-    from paper_2510_25979_amd import synth, synthdb
 
-    ac.lib()
+def apply_kernel_name(w):
+    if w.map_dtype != "bf16":
+        return "apply_f32_kernel"
+    return "apply_bf16_kernel" if w.seq_len <= 128 else "apply_bf16_long_kernel"
+
+
+def exact_kernel_name(w):
+    if w.map_dtype != "bf16":
+        return "exact_f32_kernel"
+    return "exact_bf16_kernel (resident)" if w.seq_len <= 128 else "exact_bf16_kernel (streaming)"
+
+
+# --------------------------------------------------------------------- timing helpers
+
+def ev():
+    return torch.cuda.Event(enable_timing=True)
+
+
+def event_ms(fn, steps, warmup):
+    """Mean time of fn() from HIP events on the stream the library launches on."""
+    for _ in range(warmup):
+        fn()
+    marks = [(ev(), ev()) for _ in range(steps)]
+    torch.cuda.synchronize()
+    for a, b in marks:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return sum(a.elapsed_time(b) for a, b in marks) / steps
+
+
+def graph_of(fn):
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            fn()
+    torch.cuda.synchronize()
+    return g
+
+
+def wall_ms(fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+# --------------------------------------------------------------------- one HBM-resident workload
+
+def run_resident(ac, synth, synthdb, traffic, args, cfg, *, extras=False):
+    """The whole step of one HBM-resident workload.  Returns the record of that workload; with
+    `extras` (headline workload) also per-layer mode, projector and database building."""
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    w = synth.WORKLOADS[args.workload]
-    if w.maps_on_host:
-        print("bench.py: the host-resident workload is a parity case, not a bench line",
-              file=sys.stderr)
-        sys.exit(2)
-    if args.entries:
+    w = synth.WORKLOADS[cfg]
+    if args.entries and cfg == args.workload:
         w = w.scaled(n_entries=args.entries, n_emb=args.entries)
     B, L, Hq, Hkv, S, D = w.batch, w.n_layers, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim
     dt = synth.torch_dtype(w.map_dtype)
-
-    # ---------------------------------------------------------------- inputs, resident in HBM
     t0 = time.time()
     emb, raw, map_of = synth.make_embeddings(w, dev)
     q, planted = synth.make_queries(w, raw, dev)
     del raw
     log(f"workload {w.name}: {w.n_entries} map entries, dense {w.entry_bytes / 2**20:.0f} MiB each")
-    store = synthdb.SynthMapStore(w, dev, layout=args.layout, log=log)
-    maps, packed, db_bytes = store.maps, store.packed, store.stored_bytes
-    log(f"stored {'packed' if packed else 'dense'}: {db_bytes / 2**30:.1f} GiB")
+    store = synthdb.SynthMapStore(w, dev, layout=args.layout)
+    layout = "packed" if store.packed else "dense"
     Q, K, V = synth.make_qkv(w, dev)
     O = torch.zeros(B, L, Hq, S, D, dtype=dt, device=dev)
-    O_exact = torch.zeros(B, L, Hq, S, D, dtype=dt, device=dev)
     torch.cuda.synchronize()
-    log(f"inputs ready in {time.time() - t0:.1f} s")
+    log(f"  stored {layout}: {store.stored_bytes / 2**30:.1f} GiB; inputs ready in {time.time() - t0:.1f} s")
 
-    db = ac.attncache_build_db(emb, maps, n_kv_heads=Hkv, head_dim=D, causal=w.causal, map_of=map_of,
-                               seq_len=S)
+    db = ac.attncache_build_db(emb, store.maps, n_kv_heads=Hkv, head_dim=D, causal=w.causal,
+                               map_of=map_of, seq_len=S)
     ws = torch.empty(ac.attncache_workspace_bytes(db.desc, B, w.k), dtype=torch.uint8, device=dev)
     idx = torch.empty(B, w.k, dtype=torch.int32, device=dev)
     score = torch.empty(B, w.k, dtype=torch.float32, device=dev)
@@ -134,14 +154,12 @@ def main():
     # layers fold into heads for the recompute branch: [B][L][H][S][D] == [B][L*H][S][D]
     Qf, Kf, Vf = Q.view(B, L * Hq, S, D), K.view(B, L * Hkv, S, D), V.view(B, L * Hkv, S, D)
     Of = O.view(B, L * Hq, S, D)
-    Oef = O_exact.view(B, L * Hq, S, D)
 
     def step():
         ac.attncache_search(db, q, w.k, w.theta, idx, score, hit, ws)
         ac.attncache_apply(db, hit, V, O)
         ac.attention_exact(Qf, Kf, Vf, Of, causal=w.causal, row_sel=hit)   # misses only
 
-    ev = lambda: torch.cuda.Event(enable_timing=True)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -153,8 +171,7 @@ def main():
     k_ev = [(ev(), ev(), ev(), ev()) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
-    for i in range(args.steps):
-        e0, e1, e2, e3 = k_ev[i]
+    for e0, e1, e2, e3 in k_ev:
         e0.record()
         ac.attncache_search(db, q, w.k, w.theta, idx, score, hit, ws)
         e1.record()
@@ -163,9 +180,8 @@ def main():
         ac.attention_exact(Qf, Kf, Vf, Of, causal=w.causal, row_sel=hit)
         e3.record()
     torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t_start) * 1e3
-    ms_per_step_eager = wall_ms / args.steps
-    ms_per_step = ms_per_step_eager
+    ms_eager = (time.perf_counter() - t_start) * 1e3 / args.steps
+    ms_step = ms_eager
     search_ms = sum(a.elapsed_time(b) for a, b, _, _ in k_ev) / args.steps
     apply_ms = sum(b.elapsed_time(c) for _, b, c, _ in k_ev) / args.steps
     miss_ms = sum(c.elapsed_time(d) for _, _, c, d in k_ev) / args.steps
@@ -173,154 +189,24 @@ def main():
     # ------------------- the same K steps as replays of one HIP graph (no per-launch host work)
     if args.launch == "graph":
         O_eager = O.clone()
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(graph, stream=side):
-                step()
-        torch.cuda.synchronize()
-        for _ in range(max(1, args.warmup)):
-            graph.replay()
-        torch.cuda.synchronize()
-        t_start = time.perf_counter()
-        for _ in range(args.steps):
-            graph.replay()
-        torch.cuda.synchronize()
-        ms_per_step = (time.perf_counter() - t_start) * 1e3 / args.steps
+        graph = graph_of(step)
+        ms_step = wall_ms(graph.replay, args.steps, max(1, args.warmup))
         assert torch.equal(O, O_eager), "graph replay and eager step disagree"
-        del O_eager
+        del O_eager, graph
 
-    # ------------- per-layer mode (the finer-grained variant of "Baselines" / the time-breakdown table): L x (search, reuse, exact)
-    per_layer = None
-    if args.per_layer:
-        Ql = [Q[:, l].contiguous() for l in range(L)]
-        Kl = [K[:, l].contiguous() for l in range(L)]
-        Vl = [V[:, l:l + 1].contiguous() for l in range(L)]
-        Ol = [torch.zeros(B, 1, Hq, S, D, dtype=dt, device=dev) for _ in range(L)]
-        hit_l = torch.empty(L, B, dtype=torch.int32, device=dev)
-
-        def chain():
-            for l in range(L):
-                ac.attncache_search(db, q, w.k, w.theta, idx, score, hit_l[l], ws)
-                ac.attncache_apply(db, hit_l[l], Vl[l], Ol[l], layer_begin=l, layer_count=1)
-                ac.attention_exact(Ql[l], Kl[l], Vl[l].view(B, Hkv, S, D), Ol[l].view(B, Hq, S, D),
-                                   causal=w.causal, row_sel=hit_l[l])
-
-        chain()
-        torch.cuda.synchronize()
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        graph_l = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(graph_l, stream=side):
-                chain()
-        torch.cuda.synchronize()
-        times = {}
-        for name, fn in (("graph", graph_l.replay), ("eager", chain)):
-            for _ in range(max(1, args.warmup)):
-                fn()
-            torch.cuda.synchronize()
-            t_start = time.perf_counter()
-            for _ in range(args.steps):
-                fn()
-            torch.cuda.synchronize()
-            times[name] = (time.perf_counter() - t_start) * 1e3 / args.steps
-        assert torch.equal(torch.cat(Ol, 1), O), "per-layer chain and whole-model step disagree"
-        per_layer = {"ms_per_step": times["graph"], "ms_per_step_eager": times["eager"],
-                     "tokens_per_s": B * S / (times["graph"] * 1e-3), "layers": L,
-                     "launches_per_step": 4 * L if w.k == 1 else 5 * L}
-        del Ql, Kl, Vl, Ol
-
-    # ------------------------- search alone on the million-row index of the over-HBM workload
-    index_probe = None
-    if args.index_probe:
-        w5 = synth.WORKLOADS[5]
-        gi = torch.Generator(device=dev).manual_seed(synth.seed_for(w5, 1))
-        big = torch.randn(w5.n_emb, w5.emb_dim, generator=gi, device=dev)
-        big = (big / big.norm(dim=-1, keepdim=True)).half()
-        tiny_maps = torch.zeros(16, 1, 1, 32, 32, dtype=torch.bfloat16, device=dev)
-        big_db = ac.attncache_build_db(big, tiny_maps, n_kv_heads=1, head_dim=64,
-                                       map_of=(torch.arange(w5.n_emb, device=dev) % 16).int())
-        index_probe = {"rows": w5.n_emb, "dim": w5.emb_dim, "dtype": "f16"}
-        for nq in (256, 64):
-            rows = torch.randint(0, w5.n_emb, (nq,), generator=gi, device=dev)
-            qq = big[rows].float() + 0.005 * torch.randn(nq, w5.emb_dim, generator=gi, device=dev)
-            qq = (qq / qq.norm(dim=-1, keepdim=True)).half()
-            wsb = torch.empty(ac.attncache_workspace_bytes(big_db.desc, nq, 1), dtype=torch.uint8,
-                              device=dev)
-            i_b = torch.empty(nq, 1, dtype=torch.int32, device=dev)
-            s_b = torch.empty(nq, 1, dtype=torch.float32, device=dev)
-            h_b = torch.empty(nq, dtype=torch.int32, device=dev)
-            for _ in range(max(1, args.warmup)):
-                ac.attncache_search(big_db, qq, 1, w5.theta, i_b, s_b, h_b, wsb)
-            torch.cuda.synchronize()
-            assert torch.equal(i_b[:, 0].long(), rows), "planted rows of the large index not found"
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(args.steps):
-                ac.attncache_search(big_db, qq, 1, w5.theta, i_b, s_b, h_b, wsb)
-            e1.record()
-            torch.cuda.synchronize()
-            us = e0.elapsed_time(e1) / args.steps * 1e3
-            index_probe[f"B{nq}"] = {
-                "us": us, "qps": nq / us * 1e6,
-                "hbm_frac": 2.0 * w5.n_emb * w5.emb_dim / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                "mfma_frac": 2.0 * nq * w5.n_emb * w5.emb_dim / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
-        big_db.close()
-        del big, tiny_maps
-
-    # ------------------------- feature projector in front of the search (Algorithm 1), on request
-    projector = None
-    if args.projector and w.emb_dtype == "f16":
-        dm, hid, E = Hq * D, Hq * D // 4, w.emb_dim
-        gp = torch.Generator(device=dev).manual_seed(synth.seed_for(w, 9))
-        hs = [torch.randn(B, S, dm, generator=gp, device=dev).to(torch.bfloat16) for _ in range(4)]
-        W1 = torch.randn(hid, dm, generator=gp, device=dev) / dm ** 0.5
-        W2 = torch.randn(E, hid, generator=gp, device=dev) / hid ** 0.5
-        b1 = 0.1 * torch.randn(hid, generator=gp, device=dev)
-        b2 = 0.1 * torch.randn(E, generator=gp, device=dev)
-        pws = torch.empty(ac.attncache_project_workspace_bytes(B, dm, hid, E), dtype=torch.uint8,
-                          device=dev)
-        feat = torch.empty(B, E, dtype=torch.float16, device=dev)
-
-        def project_all():
-            for h in hs:
-                ac.attncache_project(h, W1, b1, W2, b2, feat, pws)
-
-        project_all()
-        torch.cuda.synchronize()
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        graph_p = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(graph_p, stream=side):
-                project_all()
-        torch.cuda.synchronize()
-        for _ in range(max(1, args.warmup)):
-            graph_p.replay()
-        torch.cuda.synchronize()
-        t_start = time.perf_counter()
-        for _ in range(args.steps):
-            graph_p.replay()
-        torch.cuda.synchronize()
-        p_ms = (time.perf_counter() - t_start) * 1e3 / args.steps / len(hs)
-        projector = {"ms": p_ms, "model_dim": dm, "hidden_dim": hid, "emb_dim": E, "launches": 4,
-                     "dtype": "f32 (bf16 hidden states in)",
-                     "hidden_state_GBs": B * S * dm * 2 / (p_ms * 1e-3) / 1e9}
-        del hs, W1, W2, pws
+    rec_extras = {}
+    if extras and args.extras:
+        rec_extras["per_layer_mode"] = run_per_layer(ac, args, w, db, q, idx, score, ws, Q, K, V, O)
+        if w.emb_dtype == "f16":
+            rec_extras["projector"] = run_projector(ac, synth, args, w)
+        rec_extras["insert"] = run_insert(ac, args, w, Q, K, V)
 
     # ----------------------------------------- the denominator: exact attention on every query
-    for _ in range(max(1, args.warmup // 2)):
-        ac.attention_exact(Qf, Kf, Vf, Oef, causal=w.causal)
-    x_ev = [(ev(), ev()) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    for a, b in x_ev:
-        a.record()
-        ac.attention_exact(Qf, Kf, Vf, Oef, causal=w.causal)
-        b.record()
-    torch.cuda.synchronize()
-    exact_ms = sum(a.elapsed_time(b) for a, b in x_ev) / args.steps
+    O_exact = torch.zeros(B, L, Hq, S, D, dtype=dt, device=dev)
+    Oef = O_exact.view(B, L * Hq, S, D)
+    exact_ms = event_ms(lambda: ac.attention_exact(Qf, Kf, Vf, Oef, causal=w.causal), args.steps,
+                        max(1, args.warmup // 2))
+    del O_exact, Oef
 
     if args.copy_probe:
         probe_src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -331,86 +217,440 @@ def main():
         del probe_src, probe_dst
 
     tokens = B * S
-    a_bytes = apply_algorithmic_bytes(w, n_hits)
-    x_bytes = exact_algorithmic_bytes(w, B)
-    x_flops_causal = 2.0 * S * S * D * B * L * Hq if w.causal else 4.0 * S * S * D * B * L * Hq
+    a_bytes = apply_bytes(w, n_hits)
+    a_dense = apply_bytes(w, n_hits, dense_equivalent=True)
     achieved = a_bytes / (apply_ms * 1e-3) / 1e9
-    result = {
-        "metric": "prefill attention tokens/s (search + map reuse + exact on misses, one step)",
-        "value": tokens / (ms_per_step * 1e-3),
-        "unit": "tokens/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
-        "ms_per_step_eager": ms_per_step_eager,
-        "launch": "hip graph replay" if args.launch == "graph" else "eager library calls",
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "bf16" if w.map_dtype == "bf16" else "f32",
-        "data": "synthetic",
+    reading = traffic.lookup(apply_kernel_name(w), w.name, layout) if not args.entries else None
+    x_s = exact_ms * 1e-3
+    rec = {
+        "value": tokens / (ms_step * 1e-3), "unit": "tokens/s",
+        "ms_per_step": ms_step, "ms_per_step_eager": ms_eager,
         "config": {"workload": w.name, "layers": L, "q_heads": Hq, "kv_heads": Hkv, "head_dim": D,
-                   "seq_len": S, "batch": B, "db_entries": w.n_entries,
-                   "map_layout": "packed" if packed else "dense",
+                   "seq_len": S, "batch": B, "db_entries": w.n_entries, "map_layout": layout,
                    "db_gib_dense": round(w.n_entries * w.entry_bytes / 2**30, 1),
-                   "db_gib_stored": round(db_bytes / 2**30, 1), "emb": [w.n_emb, w.emb_dim],
+                   "db_gib_stored": round(store.stored_bytes / 2**30, 1), "emb": [w.n_emb, w.emb_dim],
                    "k": w.k, "theta": w.theta, "hit_rate": n_hits / B},
         "breakdown_ms": {"search": search_ms, "apply": apply_ms, "exact_on_misses": miss_ms,
                          "exact_all_queries": exact_ms},
         "reuse_tokens_per_s": n_hits * S / (apply_ms * 1e-3) if n_hits else None,
-        "exact_tokens_per_s": tokens / (exact_ms * 1e-3),
+        "exact_tokens_per_s": tokens / x_s,
         "speedup_reuse_vs_exact": (exact_ms / apply_ms) * (n_hits / B) if n_hits else None,
         "search_qps": B / (search_ms * 1e-3),
-        "roofline": {"kernel": "apply_bf16_kernel" if w.map_dtype == "bf16" else "apply_f32_kernel",
-                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": (MEASURED_TRAFFIC_RATIO[(w.name, "packed" if packed else "dense")]
-                                 * a_bytes if (w.name, "packed" if packed else "dense")
-                                 in MEASURED_TRAFFIC_RATIO and not args.entries else None),
-                     "algorithmic_bytes_per_launch": a_bytes},
-        "exact_roofline": {"kernel": "exact_bf16_kernel", "hbm_GBs": x_bytes / (exact_ms * 1e-3) / 1e9,
-                           "hbm_frac": x_bytes / (exact_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                           "mfma_TFLOPs_useful": x_flops_causal / (exact_ms * 1e-3) / 1e12,
-                           "mfma_frac_useful": x_flops_causal / (exact_ms * 1e-3) / 1e12 /
+        "roofline": {"kernel": apply_kernel_name(w), "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": reading["bytes"] if reading else None,
+                     "algorithmic_bytes_per_launch": a_bytes,
+                     "dense_equivalent_GBs": a_dense / (apply_ms * 1e-3) / 1e9},
+        "exact_roofline": {"kernel": exact_kernel_name(w),
+                           "bound": "hbm" if S <= 128 else "mfma",
+                           "hbm_GBs": exact_bytes(w, B) / x_s / 1e9,
+                           "hbm_frac": exact_bytes(w, B) / x_s / 1e9 / HBM_PEAK_GBS,
+                           "mfma_TFLOPs_useful": exact_flops(w, B) / x_s / 1e12,
+                           "mfma_frac_useful": exact_flops(w, B) / x_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                           "mfma_TFLOPs_dense_equivalent": exact_flops(w, B, True) / x_s / 1e12,
+                           "mfma_frac_dense_equivalent": exact_flops(w, B, True) / x_s / 1e12 /
                            MFMA_BF16_PEAK_TFLOPS},
-        "paper_context": "paper reports 2x (2x Xeon Silver 4410Y) and 3x (A100-80GB) attention-block "
-                         "speedup, fp32 Llama-3-3B, incl. removed Q/K projections and RoPE",
+    }
+    rec.update(rec_extras)
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline_resident(w, store, q, emb, hit, Q, K, V, args)
+    else:
+        rec["cpu_baseline"] = None
+    db.close()
+    return rec
+
+
+def cpu_baseline_resident(w, store, q, emb, hit, Q, K, V, args):
+    """The oracle as it stands on the host cores: search of the whole batch, then reuse and
+    exact attention on a sample of queries (all layers and heads), scaled to the batch's hits
+    and misses."""
+    import numpy as np
+    import oracle
+    B, L, Hq, Hkv, S, D = w.batch, w.n_layers, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim
+    hit_h = hit.cpu().numpy()
+    hits = [b for b in range(B) if hit_h[b] >= 0]
+    misses = [b for b in range(B) if hit_h[b] < 0]
+    # sample sizes: about a second of oracle work per branch
+    per_query_macs = L * Hq * S * S * D
+    n_s = max(1, min(len(hits), int(4e10 // per_query_macs)))
+    f = lambda t: t.float().cpu().numpy()
+    t1 = time.perf_counter()
+    oracle.search(f(q), f(emb), k=w.k, theta=w.theta)
+    t_search = time.perf_counter() - t1
+    sel = hits[:n_s]
+    sub_maps = f(torch.stack([store.dense_entry(int(hit_h[b])) for b in sel]))
+    sub_V = f(V[sel])
+    t1 = time.perf_counter()
+    oracle.apply(sub_maps, np.arange(len(sel), dtype=np.int32), sub_V)
+    t_apply = time.perf_counter() - t1
+    del sub_maps
+    t_exact, n_x = 0.0, 0
+    if misses:
+        xs = misses[:max(1, n_s // 2)]
+        n_x = len(xs)
+        t1 = time.perf_counter()
+        oracle.attention_exact(f(Q[xs]).reshape(n_x, L * Hq, S, D), f(K[xs]).reshape(n_x, L * Hkv, S, D),
+                               f(V[xs]).reshape(n_x, L * Hkv, S, D), causal=w.causal)
+        t_exact = time.perf_counter() - t1
+    cpu_step = t_search + t_apply * len(hits) / len(sel) + (t_exact * len(misses) / n_x if n_x else 0.0)
+    scaled = len(sel) < len(hits) or (n_x and n_x < len(misses))
+    return {
+        "value": B * S / cpu_step, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+        "extrapolated": bool(scaled),
+        "sample": f"search of all {B} queries ({t_search:.2f} s) + map reuse of {len(sel)} of "
+                  f"{len(hits)} hit queries x all {L} layers x {Hq} heads ({t_apply:.2f} s)" +
+                  (f" + exact attention of {n_x} of {len(misses)} missed queries ({t_exact:.2f} s)"
+                   if n_x else "") +
+                  ("; scaled linearly to the batch" if scaled else "") +
+                  "; fp64 scalar loops, gcc -O2 -fopenmp",
     }
 
-    if per_layer is not None:
-        result["per_layer_mode"] = per_layer
-    if projector is not None:
-        result["projector"] = projector
-    if index_probe is not None:
-        result["large_index_search"] = index_probe
 
-    # ------------------------------------------- CPU oracle on a bounded sample (reported only)
+# --------------------------------------------------------------------- extras of the headline workload
+
+def run_per_layer(ac, args, w, db, q, idx, score, ws, Q, K, V, O):
+    """Per-layer mode (the finer-grained variant of the paper's "Baselines" and its per-layer time
+    table): every layer runs its own search, reuse and recompute launch; one HIP graph."""
+    B, L, Hq, Hkv, S, D = w.batch, w.n_layers, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim
+    dev, dt = Q.device, Q.dtype
+    Ql = [Q[:, l].contiguous() for l in range(L)]
+    Kl = [K[:, l].contiguous() for l in range(L)]
+    Vl = [V[:, l:l + 1].contiguous() for l in range(L)]
+    Ol = [torch.zeros(B, 1, Hq, S, D, dtype=dt, device=dev) for _ in range(L)]
+    hit_l = torch.empty(L, B, dtype=torch.int32, device=dev)
+
+    def chain():
+        for l in range(L):
+            ac.attncache_search(db, q, w.k, w.theta, idx, score, hit_l[l], ws)
+            ac.attncache_apply(db, hit_l[l], Vl[l], Ol[l], layer_begin=l, layer_count=1)
+            ac.attention_exact(Ql[l], Kl[l], Vl[l].view(B, Hkv, S, D), Ol[l].view(B, Hq, S, D),
+                               causal=w.causal, row_sel=hit_l[l])
+
+    chain()
+    torch.cuda.synchronize()
+    graph_l = graph_of(chain)
+    t_graph = wall_ms(graph_l.replay, args.steps, max(1, args.warmup))
+    t_eager = wall_ms(chain, args.steps, max(1, args.warmup))
+    assert torch.equal(torch.cat(Ol, 1), O), "per-layer chain and whole-model step disagree"
+    return {"ms_per_step": t_graph, "ms_per_step_eager": t_eager,
+            "tokens_per_s": B * S / (t_graph * 1e-3), "layers": L}
+
+
+def run_projector(ac, synth, args, w):
+    """Feature projector in front of the search (Algorithm 1): hidden states [B][S][Hq*D] bf16,
+    hidden width a quarter of that, synthetic weights.  Not part of the timed step."""
+    dev = torch.device("cuda:0")
+    B, S, Hq, D = w.batch, w.seq_len, w.n_q_heads, w.head_dim
+    dm, hid, E = Hq * D, Hq * D // 4, w.emb_dim
+    gp = torch.Generator(device=dev).manual_seed(synth.seed_for(w, 9))
+    hs = [torch.randn(B, S, dm, generator=gp, device=dev).to(torch.bfloat16) for _ in range(4)]
+    W1 = torch.randn(hid, dm, generator=gp, device=dev) / dm ** 0.5
+    W2 = torch.randn(E, hid, generator=gp, device=dev) / hid ** 0.5
+    b1 = 0.1 * torch.randn(hid, generator=gp, device=dev)
+    b2 = 0.1 * torch.randn(E, generator=gp, device=dev)
+    pws = torch.empty(ac.attncache_project_workspace_bytes(B, dm, hid, E), dtype=torch.uint8, device=dev)
+    feat = torch.empty(B, E, dtype=torch.float16, device=dev)
+
+    def project_all():
+        for h in hs:
+            ac.attncache_project(h, W1, b1, W2, b2, feat, pws)
+
+    project_all()
+    torch.cuda.synchronize()
+    graph_p = graph_of(project_all)
+    p_ms = wall_ms(graph_p.replay, args.steps, max(1, args.warmup)) / len(hs)
+    flops = 2.0 * B * (dm * hid + hid * E)
+    return {"ms": p_ms, "model_dim": dm, "hidden_dim": hid, "emb_dim": E,
+            "dtype": "f32 (bf16 hidden states in)",
+            "roofline": {"kernel": "pool_kernel (token mean; dominant of the four launches)",
+                         "bound": "hbm", "achieved": B * S * dm * 2 / (p_ms * 1e-3) / 1e9,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": B * S * dm * 2 / (p_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "note": "whole projector time against the bytes of the hidden states; "
+                                 f"the two layers add {flops / 1e9:.2f} GFLOP on the fp32 matrix cores"}}
+
+
+def run_insert(ac, args, w, Q, K, V):
+    """Database building on the device (Fig. 3, steps 2-3): the whole batch is computed and
+    remembered (maps written in the packed layout)."""
+    dev = Q.device
+    B, L, Hq, Hkv, S, D, E = (w.batch, w.n_layers, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim,
+                              w.emb_dim)
+    if w.map_dtype != "bf16":
+        return None
+    M = B
+    tile = ac.packed_tile_elems(S, w.causal)
+    maps = torch.zeros(M, L, Hq, tile, dtype=torch.bfloat16, device=dev)
+    emb = torch.zeros(M, E, dtype=torch.float16, device=dev)
+    dbi = ac.attncache_build_db(emb, maps, n_kv_heads=Hkv, head_dim=D, causal=w.causal, seq_len=S)
+    slot = torch.arange(M, dtype=torch.int32, device=dev)
+    feat = torch.zeros(B, E, dtype=torch.float16, device=dev)
+    O = torch.empty(B, L, Hq, S, D, dtype=torch.bfloat16, device=dev)
+    ms = event_ms(lambda: ac.attncache_insert(dbi, Q, K, V, O, slot=slot, feat=feat), args.steps,
+                  max(1, args.warmup))
+    dbi.close()
+    g = Hq // Hkv
+    nbytes = (S * D * 2 * (2 + 2 / g) + tile * 2) * B * L * Hq
+    return {"ms": ms, "tokens_per_s": B * S / (ms * 1e-3),
+            "roofline": {"kernel": "insert_bf16_kernel", "bound": "hbm",
+                         "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "algorithmic_bytes_per_launch": nbytes}}
+
+
+# --------------------------------------------------------------------- search on the million-row index
+
+def run_index_search(ac, synth, args):
+    """attncache_search alone on the over-HBM workload's index (1,000,000 x 256 fp16 feature
+    vectors in HBM) at 64, 256, 512 and 1024 queries: HBM-bound below ~312 queries, matrix-bound
+    above."""
+    dev = torch.device("cuda:0")
+    w5 = synth.WORKLOADS[5]
+    N, E = w5.n_emb, w5.emb_dim
+    gi = torch.Generator(device=dev).manual_seed(synth.seed_for(w5, 1))
+    big = torch.randn(N, E, generator=gi, device=dev)
+    big = (big / big.norm(dim=-1, keepdim=True)).half()
+    tiny_maps = torch.zeros(16, 1, 1, 32, 32, dtype=torch.bfloat16, device=dev)
+    big_db = ac.attncache_build_db(big, tiny_maps, n_kv_heads=1, head_dim=64,
+                                   map_of=(torch.arange(N, device=dev) % 16).int())
+    rec = {"rows": N, "dim": E, "dtype": "f16",
+           "kernel": "search_f16_big_kernel + finalize_top1_block_kernel"}
+    q256 = None
+    for nq in (64, 256, 512, 1024):
+        rows = torch.randint(0, N, (nq,), generator=gi, device=dev)
+        qq = big[rows].float() + 0.005 * torch.randn(nq, E, generator=gi, device=dev)
+        qq = (qq / qq.norm(dim=-1, keepdim=True)).half()
+        if nq == 256:
+            q256 = qq
+        wsb = torch.empty(ac.attncache_workspace_bytes(big_db.desc, nq, 1), dtype=torch.uint8, device=dev)
+        i_b = torch.empty(nq, 1, dtype=torch.int32, device=dev)
+        s_b = torch.empty(nq, 1, dtype=torch.float32, device=dev)
+        h_b = torch.empty(nq, dtype=torch.int32, device=dev)
+        fn = lambda: ac.attncache_search(big_db, qq, 1, w5.theta, i_b, s_b, h_b, wsb)
+        us = event_ms(fn, args.steps, max(1, args.warmup)) * 1e3
+        assert torch.equal(i_b[:, 0].long(), rows), "planted rows of the large index not found"
+        nbytes = 2.0 * N * E + 2.0 * nq * E + 12.0 * nq
+        flops = 2.0 * nq * N * E
+        hbm = nbytes / (us * 1e-6) / 1e9
+        mfma = flops / (us * 1e-6) / 1e12
+        bound = "hbm" if nq < 312 else "mfma"
+        rec[f"B{nq}"] = {
+            "us": us, "qps": nq / us * 1e6,
+            "hbm_GBs": hbm, "hbm_frac": hbm / HBM_PEAK_GBS,
+            "mfma_TFLOPs": mfma, "mfma_frac": mfma / MFMA_BF16_PEAK_TFLOPS,
+            "roofline": {"bound": bound, "achieved": hbm if bound == "hbm" else mfma,
+                         "peak": HBM_PEAK_GBS if bound == "hbm" else MFMA_BF16_PEAK_TFLOPS,
+                         "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
+                         "frac": (hbm / HBM_PEAK_GBS) if bound == "hbm" else
+                         (mfma / MFMA_BF16_PEAK_TFLOPS)}}
+    if not args.no_cpu_baseline:
+        import oracle
+        t1 = time.perf_counter()
+        oracle.search(q256.float().cpu().numpy(), big.float().cpu().numpy(), k=1, theta=w5.theta)
+        t = time.perf_counter() - t1
+        rec["cpu_baseline"] = {"value": 256 / t, "unit": "queries/s", "cores": oracle.threads(),
+                               "kind": "oracle", "extrapolated": False,
+                               "sample": f"all 256 queries against all {N} rows ({t:.2f} s); fp64 "
+                                         "scalar loops, gcc -O2 -fopenmp"}
+    big_db.close()
+    return rec
+
+
+# --------------------------------------------------------------------- host-resident store
+
+def run_host_store(ac, synth, synthdb, args):
+    """Over-HBM workload: the map store in pinned host memory (as many entries as the box lets
+    one process pin), streamed with hipMemcpyAsync on a side stream under the products; the
+    million-row index in HBM.  A stream of Zipf(1.1) batches, with a small and a large entry
+    cache in HBM."""
+    dev = torch.device("cuda:0")
+    store = None
+    for n_entries in (3200, 2400, 1600, 800):
+        w = synth.WORKLOADS[5].scaled(n_entries=n_entries)
+        try:
+            store = synthdb.SynthMapStore(w, dev, layout="packed", host=True)
+            break
+        except MemoryError as e:
+            log(f"  {e}; trying fewer entries")
+    if store is None:
+        return {"skipped": "no pinned host memory available"}
+    B, L, Hq, Hkv, S, D = w.batch, w.n_layers, w.n_q_heads, w.n_kv_heads, w.seq_len, w.head_dim
+    entry_bytes = store.stored_bytes // w.n_entries
+    log(f"workload {w.name}: {w.n_entries} entries of {entry_bytes / 2**20:.0f} MiB pinned on the host "
+        f"({store.stored_bytes / 2**30:.1f} GiB)")
+    emb, raw, map_of = synth.make_embeddings(w, dev)
+    _, _, V = synth.make_qkv(w, dev)
+    O = torch.empty(B, L, Hq, S, D, dtype=torch.bfloat16, device=dev)
+    idx = torch.empty(B, 1, dtype=torch.int32, device=dev)
+    score = torch.empty(B, 1, dtype=torch.float32, device=dev)
+    hit = torch.empty(B, dtype=torch.int32, device=dev)
+    n_batches = 12
+    batches = [synth.make_queries(w, raw, dev, batch_id=i)[0] for i in range(n_batches)]
+    del raw
+
+    # plain host-to-device rate of this box from the same pinned memory (1 GiB pieces)
+    probe = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    flat = store.maps.view(-1).view(torch.uint8)
+    probe.copy_(flat[:1 << 30], non_blocking=True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for i in range(4):
+        probe.copy_(flat[i << 30:(i + 1) << 30], non_blocking=True)
+    torch.cuda.synchronize()
+    link_gbs = 4 * 1.073741824 / (time.perf_counter() - t1)
+    # and in the pieces the library copies: one entry per hipMemcpyAsync, entries far apart
+    ent = store.maps.view(w.n_entries, -1)
+    slots = probe[:8 * entry_bytes].view(torch.bfloat16).view(8, -1)
+    pick = torch.randperm(w.n_entries, generator=torch.Generator().manual_seed(5))[:64].tolist()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for i, e in enumerate(pick):
+        slots[i % 8].copy_(ent[e], non_blocking=True)
+    torch.cuda.synchronize()
+    entry_gbs = len(pick) * entry_bytes / (time.perf_counter() - t1) / 1e9
+    del probe, slots
+
+    rec = {"config": {"workload": w.name, "host_entries": w.n_entries, "entries_of_the_workload": 12800,
+                      "pinned_gib": round(store.stored_bytes / 2**30, 1),
+                      "entry_mib": entry_bytes / 2**20, "index": [w.n_emb, w.emb_dim], "batch": B,
+                      "zipf": w.zipf_s, "batches": n_batches},
+           "host_link": {"plain_copy_GBs": link_gbs, "entry_sized_copies_GBs": entry_gbs,
+                         "peak_GBs": HOST_LINK_PEAK_GBS, "frac": link_gbs / HOST_LINK_PEAK_GBS}}
+    for n_slots in (96, 1024):
+        staging = torch.empty(n_slots * entry_bytes, dtype=torch.uint8, device=dev)
+        side = torch.cuda.Stream()
+        db = ac.attncache_build_db(emb, store.maps, n_kv_heads=Hkv, head_dim=D, causal=w.causal,
+                                   map_of=map_of, seq_len=S, staging=staging, side_stream=side)
+        ws = torch.empty(ac.attncache_workspace_bytes(db.desc, B, 1), dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        t_batches, distinct = [], []
+        for q in batches:
+            t1 = time.perf_counter()
+            ac.attncache_search(db, q, 1, w.theta, idx, score, hit, ws)
+            hit_host = hit.cpu()                 # the host schedules one copy per distinct entry
+            ac.attncache_apply(db, hit_host, V, O)
+            torch.cuda.synchronize()
+            t_batches.append((time.perf_counter() - t1) * 1e3)
+            distinct.append(len(set(hit_host.tolist())))
+        lookups, copies = ac.attncache_cache_stats(db)
+        # the same last batch again with every entry it needs in the cache: products only
+        t_cached = None
+        if n_slots >= distinct[-1]:
+            t1 = time.perf_counter()
+            ac.attncache_apply(db, hit_host, V, O)
+            torch.cuda.synchronize()
+            t_cached = (time.perf_counter() - t1) * 1e3
+        total_ms = sum(t_batches)
+        copy_ms = copies * entry_bytes / (entry_gbs * 1e9) * 1e3    # the same copies with nothing else
+        rec[f"cache_{n_slots}_slots"] = {
+            "cache_gib": round(n_slots * entry_bytes / 2**30, 2),
+            "ms_per_batch": total_ms / n_batches, "ms_first_batch": t_batches[0],
+            "tokens_per_s": n_batches * B * S / (total_ms * 1e-3),
+            "distinct_entries_per_batch": sum(distinct) / n_batches,
+            "lookups": lookups, "copies": copies, "cache_hit_rate": 1.0 - copies / lookups,
+            "h2d_GBs": copies * entry_bytes / (total_ms * 1e-3) / 1e9,
+            "h2d_frac_of_link_peak": copies * entry_bytes / (total_ms * 1e-3) / 1e9 / HOST_LINK_PEAK_GBS,
+            "copy_only_ms_per_batch": copy_ms / n_batches,
+            "products_only_ms_last_batch": t_cached,
+            # share of the products' time that ran under the copies
+            "overlap": (None if t_cached is None else
+                        max(0.0, min(1.0, (copy_ms / n_batches + t_cached - total_ms / n_batches) / t_cached))),
+        }
+        db.close()
+        del staging
     if not args.no_cpu_baseline:
         import numpy as np
         import oracle
-        n_s = B   # one whole step of the workload
-        hit_h = hit.cpu().numpy()
-        sel = [b for b in range(B) if hit_h[b] >= 0][:n_s]
+        hit_h = hit_host.numpy()
+        sel = list(range(4))
+        f = lambda t: t.float().cpu().numpy()
+        sub = f(torch.stack([store.dense_entry(int(hit_h[b])) for b in sel]))
         t1 = time.perf_counter()
-        oracle.search(q.float().cpu().numpy(), emb.float().cpu().numpy(), k=w.k, theta=w.theta)
-        t_search = time.perf_counter() - t1
-        dense_hits = torch.stack([store.dense_entry(int(hit_h[b])) for b in sel])
-        sub_maps = dense_hits.float().cpu().numpy()
-        sub_V = V[sel].float().cpu().numpy()
-        t1 = time.perf_counter()
-        oracle.apply(sub_maps, np.arange(len(sel), dtype=np.int32), sub_V)
-        t_apply = time.perf_counter() - t1
-        cpu_step = t_apply + t_search * len(sel) / B
-        result["cpu_baseline"] = {
-            "value": len(sel) * S / cpu_step, "unit": "tokens/s", "cores": oracle.threads(),
-            "kind": "oracle",
-            "sample": f"search of all {B} queries ({t_search:.2f} s) + map reuse of {len(sel)} "
-                      f"queries x all {L} layers x {Hq} heads ({t_apply:.2f} s); fp64 scalar loops",
-        }
-    else:
-        result["cpu_baseline"] = None
-    db.close()
+        oracle.apply(sub, np.arange(len(sel), dtype=np.int32), f(V[sel]))
+        t = time.perf_counter() - t1
+        rec["cpu_baseline"] = {"value": len(sel) * S / t, "unit": "tokens/s (map reuse only)",
+                               "cores": oracle.threads(), "kind": "oracle", "extrapolated": True,
+                               "sample": f"map reuse of {len(sel)} of {B} queries x all {L} layers x "
+                                         f"{Hq} heads ({t:.2f} s), rate taken as the batch's; the search "
+                                         "is timed under million-row-index-search"}
+    store.close()
+    return rec
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=2,
+                    help="headline workload 2..4 (default 2, the one `value` is quoted on)")
+    ap.add_argument("--workloads", default="all",
+                    help="which records to produce: 'all' (default) or a comma list of 2,3,4,index,host; "
+                         "the headline workload is always included")
+    ap.add_argument("--no-extras", dest="extras", action="store_false",
+                    help="skip per-layer mode, projector and database building on the headline workload")
+    ap.add_argument("--entries", type=int, default=0, help="override the headline workload's map entries")
+    ap.add_argument("--layout", choices=["packed", "dense"], default="packed",
+                    help="storage layout of the map database (default: packed)")
+    ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
+                    help="how the K timed steps are issued: replays of one captured HIP graph of "
+                         "the step (default), or one library call after the other")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch one plain 1 GiB device copy per workload (a kernel of known HBM "
+                         "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    if args.workload not in (2, 3, 4):
+        print("bench.py: the headline workload is 2, 3 or 4 (1 is a correctness case, 5 is reported "
+              "under workloads.over-hbm-database)", file=sys.stderr)
+        sys.exit(2)
+
+    from paper_2510_25979_amd import binding as ac
+    from paper_2510_25979_amd import synth, synthdb, traffic
+
+    ac.lib()
+    torch.cuda.set_device(0)
+    want = ({"2", "3", "4", "index", "host"} if args.workloads == "all"
+            else set(x.strip() for x in args.workloads.split(",") if x.strip()))
+
+    head = run_resident(ac, synth, synthdb, traffic, args, args.workload, extras=True)
+    result = {
+        "metric": "prefill attention tokens/s (search + map reuse + exact on misses, one step)",
+        "value": head["value"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "ms_per_step_eager": head["ms_per_step_eager"],
+        "launch": "hip graph replay" if args.launch == "graph" else "eager library calls",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+    }
+    for k in ("config", "breakdown_ms", "reuse_tokens_per_s", "exact_tokens_per_s",
+              "speedup_reuse_vs_exact", "search_qps", "roofline", "exact_roofline", "cpu_baseline"):
+        result[k] = head[k]
+    result["paper_context"] = ("paper reports 2x (2x Xeon Silver 4410Y) and 3x (A100-80GB) attention-block "
+                               "speedup, fp32 Llama-3-3B, incl. removed Q/K projections and RoPE")
+    others = {}
+    for k in ("per_layer_mode", "projector", "insert"):
+        if head.get(k) is not None:
+            others[k] = head[k]
+    torch.cuda.empty_cache()
+    for cfg in (2, 3, 4):
+        if cfg != args.workload and str(cfg) in want:
+            rec = run_resident(ac, synth, synthdb, traffic, args, cfg)
+            others[rec["config"]["workload"]] = rec
+            torch.cuda.empty_cache()
+    if "index" in want:
+        others["million-row-index-search"] = run_index_search(ac, synth, args)
+        torch.cuda.empty_cache()
+    if "host" in want:
+        others["over-hbm-database"] = run_host_store(ac, synth, synthdb, args)
+    result["workloads"] = others
     print(json.dumps(result))
 
 
