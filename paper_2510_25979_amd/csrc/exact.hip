@@ -49,7 +49,7 @@ struct ExactArgs {
 //     c + 1 is in flight while chunk c is multiplied and one barrier per chunk suffices;
 //   * rows are unpadded; the copy permutes the 16-byte pieces of a row (a lane picks which
 //     global piece lands in its LDS slot) so that the operand reads spread over all banks:
-//     K piece p of row r sits at p ^ k_piece_swizzle(r), V piece p of row r at p ^ 2 (r mod D/16);
+//     K piece p of row r sits at p ^ k_piece_swizzle(r), V piece p of row r at p ^ v_piece_swizzle(r);
 //   * the V^T operand is fetched with the transposing LDS read (ds_read_b64_tr_b16): in a
 //     group of 16 lanes, lane i names four consecutive d of key j(i / 4) and lane t receives,
 //     for its own d, the four keys j(0..3);
@@ -75,11 +75,20 @@ __host__ __device__ constexpr int k_piece_swizzle(int r) {
   return D == 128 ? (r & 15) : ((r >> 1) & 7);
 }
 
+// Permutation of the 16-byte pieces of staged V row r.  One transposing read instruction serves
+// 32 lanes per LDS cycle: four consecutive keys j x the two 16-column halves of a 32-column
+// block x two pieces; with the key in bits 2..3 of the piece index (D = 128; D = 64 rows are
+// half as long, so the key's lowest bit already selects the bank half) those 32 accesses fall
+// on 32 different 8-byte bank pairs.
+template <int D>
+__host__ __device__ constexpr int v_piece_swizzle(int r) {
+  return D == 128 ? 4 * (r & 3) : 4 * ((r >> 1) & 1);
+}
+
 template <int D, bool CAUSAL, bool RESIDENT>
 __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel(const ExactArgs a) {
   constexpr int PPR = D / 8;                          // 16-byte pieces per row
   constexpr int NCOPY = kLChunk * PPR / kWave / 4;    // copy instructions per wave, tensor, chunk
-  constexpr int kVSwz = PPR / 2 - 1;
   __shared__ __attribute__((aligned(16))) bf16_t kb0[kLChunk * D];
   __shared__ __attribute__((aligned(16))) bf16_t vb0[kLChunk * D];
   __shared__ __attribute__((aligned(16))) bf16_t kb1[kLChunk * D];
@@ -91,6 +100,11 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
   const int il = lane & 31, kh = lane >> 5;
   const int S = a.S, g = a.Hq / a.Hkv;
+  // The scale as a scalar register written by a vector instruction: a register that comes
+  // straight from a scalar load makes the compiler wait for "all scalar and LDS traffic" before
+  // its first use in a loop iteration, which drains the operand reads in flight.
+  const float scale_log2e = __builtin_bit_cast(
+      float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, a.scale_log2e) + (lane & 0)));
   // Sequences of up to 128 keys are RESIDENT: both 64-key chunks of K and V sit in the two
   // stages for the whole tile, the workgroup walks all heads_per_wg query heads that share
   // them, and between the one barrier after the copy and the end of the tile the four waves
@@ -109,7 +123,7 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
   const int slot0 = kWave * wave + lane;
   const int crow = slot0 / PPR, cpos = slot0 % PPR;
   const int kpiece = cpos ^ k_piece_swizzle<D>(crow);   // global piece that lands in this lane's slot
-  const int vpiece = cpos ^ (2 * (crow & kVSwz));
+  const int vpiece = cpos ^ v_piece_swizzle<D>(crow);
   // Running source pointers, one per tensor, advanced by one chunk after each use (cheaper
   // than rebuilding 64-bit addresses from the chunk index every time).
   const bf16_t* kptr = nullptr;   // set per tile
@@ -160,7 +174,7 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
       for (int db = 0; db < D / 32; ++db) {
         const int j = 4 * kh + 8 * half + (t >> 2);
         const int d0 = 32 * db + 16 * (il >> 4) + 4 * (t & 3);
-        voff[half][db] = j * D + 8 * ((d0 >> 3) ^ (2 * (j & kVSwz))) + (d0 & 7);
+        voff[half][db] = j * D + 8 * ((d0 >> 3) ^ v_piece_swizzle<D>(j)) + (d0 & 7);
       }
   }
   auto vop = [&](const bf16_t* vb, int db, int jb, int s2) {
@@ -232,8 +246,8 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
     for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        const float e0 = __builtin_amdgcn_exp2f(fmaf(s[8 * s2 + 2 * w], a.scale_log2e, -m));
-        const float e1 = __builtin_amdgcn_exp2f(fmaf(s[8 * s2 + 2 * w + 1], a.scale_log2e, -m));
+        const float e0 = __builtin_amdgcn_exp2f(fmaf(s[8 * s2 + 2 * w], scale_log2e, -m));
+        const float e1 = __builtin_amdgcn_exp2f(fmaf(s[8 * s2 + 2 * w + 1], scale_log2e, -m));
         const uint32_t pk = pack_bf16(e0, e1);
         pw[s2][w] = pk;
         sum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, sum, false);
@@ -276,7 +290,7 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
     if (MASKED) hide(s0, c, 0);
     float m0 = m_run;
     {
-      const float cand = fmaxf(m_run, row_max(s0) * a.scale_log2e);
+      const float cand = fmaxf(m_run, row_max(s0) * scale_log2e);
       if (__any(cand > m_run + kRescaleSlack)) {
         rescale(cand);
         m0 = cand;
@@ -291,7 +305,7 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
     l_run += sum0;
     if (two) {
       if (MASKED) hide(s1, c, 1);
-      const float cand1 = fmaxf(m0, row_max(s1) * a.scale_log2e);
+      const float cand1 = fmaxf(m0, row_max(s1) * scale_log2e);
       const bool moved = __any(cand1 > m0 + kRescaleSlack);
       const float m1 = moved ? cand1 : m0;
       pv(vb, 0, p0);
