@@ -238,16 +238,15 @@ void apply_bf16_kernel(const ApplyArgs a) {
 // the matrix operand is then fetched with the transposing LDS read (ds_read_b64_tr_b16): in a
 // group of 16 lanes, lane i supplies the address of four consecutive d of key j(i/4) and lane
 // t receives, for ITS d, the four keys j(0..3) -- exactly the operand layout, no shuffles.
-// Rows are stored unpadded; 16-byte piece p of key row r sits at position p ^ 2 (r & (D/16 - 1)), which
-// spreads the four key rows one group touches over distinct banks; the copy applies the
-// swizzle by choosing which global piece each lane fetches.
+// Rows are stored unpadded; 16-byte piece p of key row r sits at position p ^ v_piece_swizzle(r),
+// which spreads the 32 lanes one LDS cycle serves over all banks; the copy applies the
+// permutation by choosing which global piece each lane fetches.
 constexpr int kOutStride = 64 + 4;   // row stride of the 16 x 64 output staging passes
 
 template <int D, bool CAUSAL, bool PACKED>
 __global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const ApplyArgs a) {
   constexpr int PPR = D / 8;                       // 16-byte pieces per V row
   constexpr int NCOPY = kChunk * PPR / kWave / 4;  // copy instructions per wave and chunk
-  constexpr int kSwz = PPR / 2 - 1;                // swizzle mask: 2 (r & kSwz) < PPR
   __shared__ __attribute__((aligned(16))) bf16_t vb0[kChunk * D];
   __shared__ __attribute__((aligned(16))) bf16_t vb1[kChunk * D];
   // Causal maps at head_dim 64: a workgroup takes a PAIR of row blocks (see below).  Its
@@ -286,10 +285,10 @@ __global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const Appl
   const int S = a.S, g = a.Hq / a.Hkv;
   const int n32 = S >> 5;
   const size_t tile_elems = PACKED ? (size_t)packed_blocks(S, CAUSAL) * 512 : (size_t)S * S;
-  const bf16_t* Vsrc = reinterpret_cast<const bf16_t*>(a.V) +
-                       (((size_t)b * a.Lc + l) * a.Hkv + h / g) * (size_t)S * D;
-  const bf16_t* At = reinterpret_cast<const bf16_t*>(a.maps) +
-                     (((size_t)entry * a.L + (a.layer_begin + l)) * a.Hq + h) * tile_elems;
+  const bf16_t* Vsrc = uniform_ptr(reinterpret_cast<const bf16_t*>(a.V) +
+                                   (((size_t)b * a.Lc + l) * a.Hkv + h / g) * (size_t)S * D);
+  const bf16_t* At = uniform_ptr(reinterpret_cast<const bf16_t*>(a.maps) +
+                                 (((size_t)entry * a.L + (a.layer_begin + l)) * a.Hq + h) * tile_elems);
 
   const int R_hi = a.n_rblk - 1 - pair, R_lo = PAIRED ? pair : R_hi;   // heaviest first
   const int n_hi = CAUSAL ? R_hi + 1 : (S + kChunk - 1) / kChunk;
@@ -310,10 +309,12 @@ __global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const Appl
       : (unsigned)((32 * rb32 + il) * S + 8 * kh);
   };
   const unsigned piece_row_hi = piece_row_of(R_hi), piece_row_lo = piece_row_of(R_lo);
+  // (the column step is uniform over the wave: it goes into the scalar base, the lane's own
+  // offset stays one register per row block whatever the step)
   auto piece = [&](int R, int ks) -> const u32x4* {
     const unsigned piece_row = R == R_hi ? piece_row_hi : piece_row_lo;
-    const unsigned off = PACKED ? piece_row + (unsigned)ks * 256u : piece_row + (unsigned)ks * 16u;
-    return reinterpret_cast<const u32x4*>(At + off);
+    const char* step_base = reinterpret_cast<const char*>(At + (size_t)ks * (PACKED ? 256 : 16));
+    return reinterpret_cast<const u32x4*>(step_base + 2u * piece_row);   // 32-bit BYTE offset
   };
   // column steps of chunk c this wave needs
   auto steps = [&](int R, int c) {
@@ -339,7 +340,7 @@ __global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const Appl
   // 2048 elements on both sides, so one 32-bit lane offset serves all of them.  Rows past the
   // end of V (ragged last chunk) repeat the last row: finite values that are never multiplied.
   const int slot0 = kWave * wave + lane;
-  const unsigned copy_off = (unsigned)((slot0 / PPR) * D + 8 * ((slot0 % PPR) ^ (2 * ((slot0 / PPR) & kSwz))));
+  const unsigned copy_off = (unsigned)((slot0 / PPR) * D + 8 * ((slot0 % PPR) ^ v_piece_swizzle<D>(slot0 / PPR)));
   const bf16_t* vrun = Vsrc;   // chunk after chunk, in order: a running (scalar) source pointer
   auto copy_v = [&](bf16_t* buf, int c) {
     const int nj = min(kChunk, S - c * kChunk);
@@ -355,7 +356,7 @@ __global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const Appl
       for (int i = 0; i < NCOPY; ++i) {
         const int slot = slot0 + 4 * kWave * i;
         const int row = slot / PPR, pos = slot % PPR;
-        const int src_piece = pos ^ (2 * (row & kSwz));
+        const int src_piece = pos ^ v_piece_swizzle<D>(row);
         __builtin_amdgcn_global_load_lds(src + (size_t)min(row, nj - 1) * D + 8 * src_piece,
                                          buf + kWave * 8 * (wave + 4 * i), 16, 0, 0);
       }
@@ -371,7 +372,7 @@ __global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const Appl
   // transposing operand fetch: rows d = 32 db + il of V^T, contraction slots (kh, e) = key
   // 16 ks + 8 kh + e.  Lane i of a 16-lane group names key row 16 ks + 8 kh + i / 4 (+ 4 for
   // the second half) and the four d starting at 32 db + 16 (il / 16) + 4 (i % 4).  The row's
-  // swizzle only depends on (key & 7), i.e. not on ks: one element offset per (half, db) is
+  // permutation only depends on (key & 3), i.e. not on ks: one element offset per (half, db) is
   // kept in a register and ks enters as a constant.
   typedef short s16x4 __attribute__((ext_vector_type(4)));
   int voff[2][D / 32];
@@ -383,7 +384,7 @@ __global__ __launch_bounds__(kThreads, 2) void apply_bf16_long_kernel(const Appl
       for (int db = 0; db < D / 32; ++db) {
         const int j = 8 * kh + 4 * half + (t >> 2);               // key row for ks = 0
         const int d0 = 32 * db + 16 * (il >> 4) + 4 * (t & 3);     // first of this lane's four d
-        voff[half][db] = j * D + 8 * ((d0 >> 3) ^ (2 * (j & kSwz))) + (d0 & 7);
+        voff[half][db] = j * D + 8 * ((d0 >> 3) ^ v_piece_swizzle<D>(j)) + (d0 & 7);
       }
   }
   auto vop = [&](const bf16_t* buf, int db, int ks) {

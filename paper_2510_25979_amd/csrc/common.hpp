@@ -43,10 +43,36 @@ __device__ __forceinline__ int mfma_row(int v, int kh) {
   return 8 * (v >> 2) + 4 * kh + (v & 3);
 }
 
+// A pointer that is the same in every lane, moved into scalar registers: loads through it can
+// then take "scalar base + 32-bit lane offset" addresses instead of a 64-bit address per lane.
+template <typename T>
+__device__ __forceinline__ const T* uniform_ptr(const T* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  // (rebuilt as a GLOBAL pointer: the round trip through integers would otherwise leave a
+  // generic one, and loads through it would be flat loads)
+  typedef const T __attribute__((address_space(1))) * global_ptr;
+  return (const T*)(global_ptr)(((uint64_t)hi << 32) | lo);
+}
+
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   typedef bf16_t bf16x2 __attribute__((ext_vector_type(2)));
   bf16x2 p = {(bf16_t)lo, (bf16_t)hi};  // round-to-nearest-even
   return __builtin_bit_cast(uint32_t, p);
+}
+
+// Permutation of the 16-byte pieces of a V row staged row-major in LDS for the transposing
+// read (ds_read_b64_tr_b16): piece p of key row r sits at position p ^ v_piece_swizzle(r).  One
+// such read instruction serves 32 lanes per LDS cycle: four consecutive keys x the two
+// 16-column halves of a 32-column block x two pieces.  With the key in bits 2..3 of the piece
+// index (D = 128; at D = 64 a row is half as long, so the key's lowest bit already selects the
+// bank half and only its second bit enters) those 32 accesses fall on 32 different 8-byte bank
+// pairs.  Unchanged by r + 4, so a copy that advances by whole multiples of four rows keeps one
+// lane offset.
+template <int D>
+__host__ __device__ constexpr int v_piece_swizzle(int r) {
+  return D == 128 ? 4 * (r & 3) : 4 * ((r >> 1) & 1);
 }
 
 // Stage V[j0 .. j0+nj)[0..D) (row-major, row stride D) into LDS transposed:
@@ -119,6 +145,50 @@ __device__ __forceinline__ void store_tile_bf16(const f32x16 (&acc)[D / 32], flo
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
+}
+
+// The same, for kernels whose big LDS tiles stay in use while results leave: the wave's 32 x D
+// result goes out in 16-row x 64-column passes through a SMALL wave-private buffer
+// (16 x kSmallOutStride elements = 2176 bytes); every global store still covers whole 128-byte
+// lines.
+constexpr int kSmallOutStride = 64 + 4;
+template <int D>
+__device__ __forceinline__ void store_tile_bf16_small(const f32x16 (&acc)[D / 32], float mul,
+                                                      bf16_t* __restrict__ ost,
+                                                      bf16_t* __restrict__ dst, int lane) {
+  const int il = lane & 31, kh = lane >> 5;
+#pragma unroll
+  for (int rh = 0; rh < 2; ++rh)
+#pragma unroll
+    for (int dh = 0; dh < D / 64; ++dh) {
+      if ((il >> 4) == rh) {
+#pragma unroll
+        for (int dbp = 0; dbp < 2; ++dbp)
+#pragma unroll
+          for (int vq = 0; vq < 4; ++vq) {
+            const f32x16& t = acc[2 * dh + dbp];
+            u32x2 w;
+            w.x = pack_bf16(t[4 * vq] * mul, t[4 * vq + 1] * mul);
+            w.y = pack_bf16(t[4 * vq + 2] * mul, t[4 * vq + 3] * mul);
+            *reinterpret_cast<u32x2*>(ost + (il & 15) * kSmallOutStride + 32 * dbp + 8 * vq + 4 * kh) = w;
+          }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int it = 0; it < 2; ++it) {
+        const int p = it * kWave + lane;
+        const int row = p >> 3, c8 = p & 7;
+        const u32x2* sp = reinterpret_cast<const u32x2*>(ost + row * kSmallOutStride + 8 * c8);
+        u32x2 lo = sp[0], hi = sp[1];
+        __builtin_nontemporal_store(
+            u32x4{lo.x, lo.y, hi.x, hi.y},
+            reinterpret_cast<u32x4*>(dst + (size_t)(16 * rh + row) * D + 64 * dh + 8 * c8));
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    }
 }
 
 }  // namespace ac

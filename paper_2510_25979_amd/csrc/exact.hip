@@ -75,16 +75,6 @@ __host__ __device__ constexpr int k_piece_swizzle(int r) {
   return D == 128 ? (r & 15) : ((r >> 1) & 7);
 }
 
-// Permutation of the 16-byte pieces of staged V row r.  One transposing read instruction serves
-// 32 lanes per LDS cycle: four consecutive keys j x the two 16-column halves of a 32-column
-// block x two pieces; with the key in bits 2..3 of the piece index (D = 128; D = 64 rows are
-// half as long, so the key's lowest bit already selects the bank half) those 32 accesses fall
-// on 32 different 8-byte bank pairs.
-template <int D>
-__host__ __device__ constexpr int v_piece_swizzle(int r) {
-  return D == 128 ? 4 * (r & 3) : 4 * ((r >> 1) & 1);
-}
-
 template <int D, bool CAUSAL, bool RESIDENT>
 __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel(const ExactArgs a) {
   constexpr int PPR = D / 8;                          // 16-byte pieces per row

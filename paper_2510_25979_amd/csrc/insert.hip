@@ -33,6 +33,7 @@ struct InsertArgs {
   const int32_t *slot, *row_sel, *key_len;
   int32_t B, M, L, layer_begin, Lc, Hq, Hkv, S;
   int32_t n_rblk, n_tiles;
+  int32_t heads_per_wg;   // query heads one workgroup walks (they share K and V)
   float scale_log2e;
 };
 
@@ -40,8 +41,9 @@ template <int D, bool CAUSAL, bool PACKED>
 __global__ __launch_bounds__(kThreads, 2) void insert_bf16_kernel(const InsertArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int KS = D + kKPadI;
-  bf16_t* ks_lds = reinterpret_cast<bf16_t*>(smem);   // [128][KS]; the output tile is staged here
+  bf16_t* ks_lds = reinterpret_cast<bf16_t*>(smem);   // [128][KS]
   bf16_t* vt = ks_lds + kChunk * KS;                  // [D][kVtStride]
+  bf16_t* ost_small = vt + D * kVtStride;             // [4][16][kSmallOutStride]: results on their way out
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -50,39 +52,35 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_kernel(const InsertAr
 
   // Workgroup ids that are equal mod 8 run on the same XCD and share its L2.  All row blocks of
   // one (item, layer, head) AND all g heads that read the same K and V get such ids, so K and
-  // V come from HBM once per group: KV group (t / g) * 8 + x for the t-th tile slot of XCD x.
+  // V come from HBM once per group.  For S <= 128 one workgroup walks all g heads of the group
+  // itself (heads_per_wg = g): K and V are staged -- and V is transposed -- once per group
+  // instead of once per query head.
   const int bid = blockIdx.x;
-  const int x = bid & 7, t = (bid >> 3) / a.n_rblk;
-  const int tile = ((t / g) * 8 + x) * g + t % g;
-  const int R = a.n_rblk - 1 - (bid >> 3) % a.n_rblk;
-  if (tile >= a.n_tiles) return;
-  const int h = tile % a.Hq;
-  const int l = (tile / a.Hq) % a.Lc;
-  const int b = tile / (a.Hq * a.Lc);
+  const int hslots = g / a.heads_per_wg;
+  const int slot_id = bid >> 3;
+  const int grp = (slot_id / (hslots * a.n_rblk)) * 8 + (bid & 7);   // (item, layer, KV head)
+  const int hslot = (slot_id / a.n_rblk) % hslots;
+  const int R = a.n_rblk - 1 - slot_id % a.n_rblk;
+  if (grp >= a.n_tiles) return;
+  const int kvh = grp % a.Hkv;
+  const int l = (grp / a.Hkv) % a.Lc;
+  const int b = grp / (a.Hkv * a.Lc);
   if (a.row_sel && a.row_sel[b] >= 0) return;
   // real tokens of this sentence in a right-padded batch: later keys get weight zero
   const int len = a.key_len ? min(max(a.key_len[b], 1), S) : S;
   const int entry = a.slot ? a.slot[b] : -1;
   const bool keep = entry >= 0 && entry < a.M;   // anything else: compute O only
 
-  const size_t kv = (((size_t)b * a.Lc + l) * a.Hkv + h / g) * (size_t)S * D;
+  const size_t kv = (((size_t)b * a.Lc + l) * a.Hkv + kvh) * (size_t)S * D;
   const bf16_t* Kt = reinterpret_cast<const bf16_t*>(a.K) + kv;
   const bf16_t* Vt_src = reinterpret_cast<const bf16_t*>(a.V) + kv;
-  const size_t qo = (((size_t)b * a.Lc + l) * a.Hq + h) * (size_t)S * D;
   const int n_chunk = CAUSAL ? R + 1 : (S + kChunk - 1) / kChunk;
   const int r0 = R * kChunk + 32 * wave;
   const bool active = r0 < S;
   const int n32 = S >> 5;
   const size_t tile_elems = PACKED ? (size_t)packed_blocks(S, CAUSAL) * 512 : (size_t)S * S;
-  bf16_t* At = reinterpret_cast<bf16_t*>(a.maps) +
-               (((size_t)(keep ? entry : 0) * a.L + (a.layer_begin + l)) * a.Hq + h) * tile_elems;
-
   u32x4 q[D / 16];
-  if (active) {
-    const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.Q) + qo + (size_t)(r0 + il) * D + 8 * kh;
-#pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) q[ks] = *reinterpret_cast<const u32x4*>(qrow + 16 * ks);
-  }
+  bf16_t* At = nullptr;   // this head's map in the store, set per head
 
   auto stage_k = [&](int c) {
     const int j0 = c * kChunk, nj = min(kChunk, S - j0);
@@ -126,13 +124,26 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_kernel(const InsertAr
     return s;
   };
 
+  for (int hl = 0; hl < a.heads_per_wg; ++hl) {
+  const int h = kvh * g + hslot * a.heads_per_wg + hl;
+  const size_t qo = (((size_t)b * a.Lc + l) * a.Hq + h) * (size_t)S * D;
+  At = reinterpret_cast<bf16_t*>(a.maps) +
+       (((size_t)(keep ? entry : 0) * a.L + (a.layer_begin + l)) * a.Hq + h) * tile_elems;
+  if (active) {
+    const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.Q) + qo + (size_t)(r0 + il) * D + 8 * kh;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) q[ks] = *reinterpret_cast<const u32x4*>(qrow + 16 * ks);
+  }
+
   // ---- pass 1: row maximum m (log2 domain, scale folded in) and row sum l of 2^(score - m)
   float m_run = -INFINITY, l_run = 0.f;
   for (int c = 0; c < n_chunk; ++c) {
-    if (c > 0) __syncthreads();
-    stage_k(c);
-    if (n_chunk == 1) stage_v(0);   // short sequences: V is staged once, next to K
-    __syncthreads();
+    if (n_chunk > 1 || hl == 0) {   // a resident chunk (S <= 128) serves every head of the group
+      if (c > 0 || hl > 0) __syncthreads();
+      stage_k(c);
+      if (n_chunk == 1) stage_v(0);   // short sequences: V is staged once, next to K
+      __syncthreads();
+    }
     const int nblk = blocks(c);
     for (int jb = 0; jb < nblk; ++jb) {
       const f32x16 s = scores(c, jb);
@@ -212,11 +223,15 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_kernel(const InsertAr
       for (int q4 = 0; q4 < 4; ++q4) *map_piece(kb, q4) = u32x2{0u, 0u};
   }
 
-  __syncthreads();   // K is dead: the output tiles are staged on top of it
-  if (active) {
-    bf16_t* Oh = reinterpret_cast<bf16_t*>(a.O) + qo + (size_t)r0 * D;
-    store_tile_bf16<D>(acc, 1.0f, ks_lds + wave * (32 * (D + 4)), Oh, lane);
+  bf16_t* Oh = reinterpret_cast<bf16_t*>(a.O) + qo + (size_t)r0 * D;
+  if (a.heads_per_wg > 1) {
+    // K and V stay staged for the next head: the result leaves through the wave's small buffer
+    if (active) store_tile_bf16_small<D>(acc, 1.0f, ost_small + wave * (16 * kSmallOutStride), Oh, lane);
+  } else {
+    __syncthreads();   // one head per workgroup: K is dead, the whole tile is staged on top of it
+    if (active) store_tile_bf16<D>(acc, 1.0f, ks_lds + wave * (32 * (D + 4)), Oh, lane);
   }
+  }   // heads of the group
 }
 
 // feature vector of item b into row slot[b] of the feature store (16-byte pieces)
@@ -233,13 +248,15 @@ __global__ __launch_bounds__(kThreads) void insert_features_kernel(const u32x4* 
     emb[(size_t)entry * pieces + p] = feat[(size_t)b * pieces + p];
 }
 
-static size_t insert_lds_bytes(int D) {
-  return (size_t)(kChunk * (D + kKPadI) + D * kVtStride) * sizeof(bf16_t);
+// the small output buffers exist only when a workgroup walks several heads
+static size_t insert_lds_bytes(int D, int heads_per_wg) {
+  return (size_t)(kChunk * (D + kKPadI) + D * kVtStride +
+                  (heads_per_wg > 1 ? 4 * 16 * kSmallOutStride : 0)) * sizeof(bf16_t);
 }
 
 template <int D, bool CAUSAL, bool PACKED>
 static hipError_t launch_insert_t(const InsertArgs& a, dim3 grid, hipStream_t stream) {
-  const size_t lds = insert_lds_bytes(D);
+  const size_t lds = insert_lds_bytes(D, a.heads_per_wg);
   hipError_t e = ensure_lds<&insert_bf16_kernel<D, CAUSAL, PACKED>>(lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((insert_bf16_kernel<D, CAUSAL, PACKED>), grid, dim3(kThreads), lds, stream, a);
@@ -271,12 +288,13 @@ hipError_t launch_insert(const InsertLaunch& p, hipStream_t stream) {
   a.B = p.B; a.M = p.M; a.L = p.L; a.layer_begin = p.layer_begin; a.Lc = p.Lc;
   a.Hq = p.Hq; a.Hkv = p.Hkv; a.S = p.S;
   a.n_rblk = (p.S + kChunk - 1) / kChunk;
-  a.n_tiles = p.B * p.Lc * p.Hq;
+  a.n_tiles = p.B * p.Lc * p.Hkv;   // KV groups: (item, layer, KV head)
   const float scale = p.scale == 0.f ? 1.0f / sqrtf((float)p.D) : p.scale;
   a.scale_log2e = scale * 1.44269504088896340736f;
   const int g = p.Hq / p.Hkv;
-  const int groups8 = (a.n_tiles / g + 7) / 8 * 8;   // KV groups, padded to a multiple of 8
-  const dim3 grid((unsigned)((size_t)groups8 * g * a.n_rblk));
+  a.heads_per_wg = a.n_rblk == 1 ? g : 1;
+  const int groups8 = (a.n_tiles + 7) / 8 * 8;   // padded to a multiple of 8
+  const dim3 grid((unsigned)((size_t)groups8 * (g / a.heads_per_wg) * a.n_rblk));
   return p.D == 64 ? launch_insert_d<64>(a, grid, p.causal, p.packed, stream)
                    : launch_insert_d<128>(a, grid, p.causal, p.packed, stream);
 }
