@@ -63,20 +63,30 @@ def lookup(kernel: str, workload: str, layout: str) -> Optional[dict]:
 
 
 def _readings(directory: str, counter: str):
-    """Counter values per dispatch, grouped by kernel name, from rocprofv3's CSV output."""
+    """(dispatch id, counter value) per dispatch, grouped by kernel name, from rocprofv3's CSV."""
     out = {}
     for f in glob.glob(os.path.join(directory, "**", "*counter_collection.csv"), recursive=True):
         for r in csv.DictReader(open(f)):
             if r["Counter_Name"] == counter:
-                out.setdefault(r["Kernel_Name"], []).append(float(r["Counter_Value"]))
+                out.setdefault(r["Kernel_Name"], []).append(
+                    (int(r.get("Dispatch_Id") or 0), float(r["Counter_Value"])))
     return out
 
 
 def _pick(readings: dict, needle: str):
-    vals = [v for k, vs in readings.items() if needle in k for v in vs]
+    vals = [v for k, vs in readings.items() if needle in k for _, v in vs]
     if not vals:
         raise SystemExit(f"no dispatch of a kernel named *{needle}* in the counter output")
     return vals
+
+
+def _probe(readings: dict) -> float:
+    """Reading of the copy probe: the LAST device copy of the run (bench.py issues it after all
+    timed work; torch's own copies of other sizes come earlier)."""
+    rows = [dv for k, vs in readings.items() if COPY_KERNEL in k for dv in vs]
+    if not rows:
+        raise SystemExit("no device copy in the counter output: run bench.py with --copy-probe")
+    return max(rows)[1]
 
 
 def main():
@@ -91,8 +101,8 @@ def main():
                          "launched on a part of the batch)")
     args = ap.parse_args()
     fetch, write = _readings(args.fetch, "FETCH_SIZE"), _readings(args.write, "WRITE_SIZE")
-    f_scale = COPY_KIB / statistics.median(_pick(fetch, COPY_KERNEL))
-    w_scale = COPY_KIB / statistics.median(_pick(write, COPY_KERNEL))
+    f_scale = COPY_KIB / _probe(fetch)
+    w_scale = COPY_KIB / _probe(write)
     agg = max if args.largest else statistics.median
     f_raw, w_raw = agg(_pick(fetch, args.kernel)), agg(_pick(write, args.kernel))
     entry = {"revision": source_revision(), "fetch_raw": f_raw, "fetch_scale": round(f_scale, 4),
