@@ -10,13 +10,18 @@ of another revision, so a changed kernel never inherits an old reading.
 Regenerate (from the repo root, on a GPU box; ``cd /tmp && export TMPDIR=/tmp`` first)::
 
     rocprofv3 --pmc FETCH_SIZE -d <dirF> -o bench --output-format csv -- \
-        python3 bench.py --workloads 2 --steps 3 --warmup 1 --no-cpu-baseline --copy-probe
+        python3 bench.py --workload 2 --workloads 2 --no-extras --steps 3 --warmup 1 \
+        --no-cpu-baseline --copy-probe
     rocprofv3 --pmc WRITE_SIZE -d <dirW> -o bench --output-format csv -- \
-        python3 bench.py --workloads 2 --steps 3 --warmup 1 --no-cpu-baseline --copy-probe
+        python3 bench.py --workload 2 --workloads 2 --no-extras --steps 3 --warmup 1 \
+        --no-cpu-baseline --copy-probe
     python3 -m paper_2510_25979_amd.traffic --fetch <dirF> --write <dirW> \
         --workload llama-3.2-1b-shaped --layout packed --kernel apply_bf16_kernel
+    python3 -m paper_2510_25979_amd.traffic --fetch <dirF> --write <dirW> \
+        --workload llama-3.2-1b-shaped --kernel exact_bf16_kernel --largest
 
-(the same with ``--workloads 3`` / ``4`` and the kernel that serves them).
+(the same with ``--workload 3 --workloads 3`` / ``4`` and the kernels that serve them:
+``apply_bf16_kernel`` and ``apply_bf16_long_kernel``).
 """
 from __future__ import annotations
 
