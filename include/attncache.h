@@ -206,7 +206,9 @@ int32_t attncache_destroy_db(attncache_db *db);
  * additions depends on the kernel that serves the shape, so two rows whose
  * exact scores differ by less than about 1e-6 relative may come out in
  * either order (rows with bit-identical feature vectors never do: the lower
- * index wins).
+ * index wins).  A query with a NaN component has no ordered scores: it is a
+ * miss (hit -1), and its idx entries are -1 (score -inf) or name rows whose
+ * score is NaN, depending on the kernel; nothing is read out of bounds.
  */
 int32_t attncache_search(const attncache_db *db, const void *q, int32_t B,
                          int32_t k, float threshold, int32_t *idx,

@@ -404,6 +404,10 @@ __global__ __launch_bounds__(kThreads) void search_valu_kernel(const SearchArgs 
 
 // ------------------------------------------------------------------- phase 2
 __device__ __forceinline__ void write_hit(const SearchArgs& a, int b, float s0, int i0) {
+  if (i0 == kIdxNone) {   // no row ranked at all (every score of the query is NaN): a miss
+    a.hit[b] = -1;
+    return;
+  }
   float sim = s0;
   if (a.metric == 1) sim = 1.0f - sqrtf(-s0);
   int entry = a.map_of ? a.map_of[i0] : i0;
@@ -424,7 +428,7 @@ __global__ __launch_bounds__(kThreads) void finalize_top1_kernel(const SearchArg
   }
   block_argmax(s, i, red_s, red_i);
   if (threadIdx.x == 0) {
-    a.idx[b] = i;
+    a.idx[b] = i == kIdxNone ? -1 : i;
     a.score[b] = s;
     write_hit(a, b, s, i);
   }
@@ -467,7 +471,7 @@ __global__ __launch_bounds__(kThreads) void finalize_top1_block_kernel(const Sea
   }
   block_argmax(rs, ri, red_s, red_i);
   if (tid == 0) {
-    a.idx[b] = ri;
+    a.idx[b] = ri == kIdxNone ? -1 : ri;
     a.score[b] = s;
     write_hit(a, b, s, ri);
   }
@@ -531,7 +535,7 @@ __global__ __launch_bounds__(kThreads) void finalize_topk_kernel(const SearchArg
     }
     block_argmax(s, i, red_s, red_i);
     if (tid == 0) {
-      a.idx[(size_t)b * a.k + r] = i;
+      a.idx[(size_t)b * a.k + r] = i == kIdxNone ? -1 : i;
       a.score[(size_t)b * a.k + r] = s;
       if (r == 0) write_hit(a, b, s, i);
     }

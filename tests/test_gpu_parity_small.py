@@ -316,6 +316,44 @@ def test_search_matches_oracle(ac, oracle_mod, case):
     assert exempt <= max(1, B * k // 50), exempt
 
 
+NAN_CASES = [
+    # N, E, B, k, dtype, metric: one per phase-1 kernel and finalising kernel
+    (1000, 256, 8, 1, torch.float16, "ip"),      # row-stationary matrix-core kernel, k = 1
+    (3000, 256, 8, 4, torch.float16, "ip"),      # the same with the re-scoring top-k
+    (50021, 256, 6, 1, torch.float16, "ip"),     # query-stationary kernel, one query block per wave
+    (60000, 128, 140, 1, torch.float16, "ip"),   # query-stationary kernel, two query blocks per wave
+    (60000, 128, 33, 3, torch.float16, "ip"),    # query-stationary kernel + re-scoring top-k
+    (777, 40, 5, 2, torch.float32, "l2"),        # vector-ALU kernel
+]
+
+
+@pytest.mark.parametrize("case", NAN_CASES, ids=lambda c: "N%d-E%d-B%d-k%d-%s-%s" % (
+    c[0], c[1], c[2], c[3], str(c[4]).split(".")[-1], c[5]))
+def test_search_query_with_nan_is_a_miss_and_the_others_are_unaffected(ac, oracle_mod, case):
+    # every score of a query that holds a NaN is NaN, so no row ever ranks: the finalising
+    # kernels must report a miss without looking up map_of at the "no row" index
+    N, E, B, k, dt, metric = case
+    g = _gen(900 + N + E + B)
+    raw = torch.randn(N, E, generator=g)
+    emb = (raw / raw.norm(dim=-1, keepdim=True)).to(dt)
+    rows = torch.randint(0, N, (B,), generator=g)
+    q = emb[rows].clone()
+    bad = [0, B - 1] if B > 1 else [0]
+    for b in bad:
+        q[b, (7 * b) % E] = float("nan")
+    m = ac.AC_IP if metric == "ip" else ac.AC_L2
+    theta = 0.9 if metric == "ip" else 0.5
+    map_of = (torch.arange(N) % 16).int()
+    idx, score, hit = _run_search(ac, emb, q, k, theta, m, map_of=map_of)
+    idx, hit = idx.cpu(), hit.cpu()
+    good = [b for b in range(B) if b not in bad]
+    for b in bad:
+        assert hit[b] == -1
+        assert ((idx[b] == -1) | ((idx[b] >= 0) & (idx[b] < N))).all()
+    assert (idx[good, 0].long() == rows[good]).all()
+    assert (hit[good].long() == map_of[rows[good]].long()).all()
+
+
 def test_search_large_database_duplicates_give_the_lowest_row(ac, oracle_mod):
     # the query-stationary kernel remembers only the winning 32-row block and the finalising
     # kernel re-scores it: copies of the best row in the same block, in another block of the
