@@ -4,8 +4,10 @@
 through HBM as read from two ``rocprofv3 --pmc`` runs (``FETCH_SIZE``, then ``WRITE_SIZE``; KiB
 per dispatch), each scaled by what the same counter reads for a plain device copy of 2^30 bytes
 issued by ``bench.py --copy-probe`` in the same run.  Every entry carries the revision of the
-kernel sources it was measured on (a hash of ``csrc/``); ``lookup`` returns nothing for an entry
-of another revision, so a changed kernel never inherits an old reading.
+kernel source it was measured on (a hash of the ``.hip`` file that defines the kernel and of
+the shared headers); ``lookup`` returns nothing for an entry of another revision, so a changed
+kernel never inherits an old reading, and a change to another kernel's file does not discard
+this one's.
 
 Regenerate (from the repo root, on a GPU box; ``cd /tmp && export TMPDIR=/tmp`` first)::
 
@@ -41,14 +43,24 @@ COPY_KERNEL = "copyBuffer"          # the runtime's device-to-device copy kernel
 COPY_KIB = 1 << 20                  # the probe copies 2^30 bytes: 2^20 KiB read, 2^20 KiB written
 
 
-def source_revision() -> str:
-    """Hash of the kernel sources: the revision a reading belongs to."""
+def source_file(kernel: str) -> str:
+    """The file under csrc/ that defines a kernel: kernels are named <file stem>_..."""
+    stem = kernel.split("_")[0]
+    name = stem + ".hip"
+    if not os.path.exists(os.path.join(HERE, "csrc", name)):
+        raise ValueError(f"no source file csrc/{name} for kernel {kernel!r}")
+    return name
+
+
+def source_revision(kernel: str) -> str:
+    """Hash of the kernel's source file and of the shared headers: the revision a reading of
+    that kernel belongs to."""
     h = hashlib.sha256()
     csrc = os.path.join(HERE, "csrc")
-    for name in sorted(os.listdir(csrc)):
-        if name.endswith((".hip", ".hpp")):
-            h.update(name.encode())
-            h.update(open(os.path.join(csrc, name), "rb").read())
+    names = [source_file(kernel)] + sorted(n for n in os.listdir(csrc) if n.endswith(".hpp"))
+    for name in names:
+        h.update(name.encode())
+        h.update(open(os.path.join(csrc, name), "rb").read())
     return h.hexdigest()[:16]
 
 
@@ -62,7 +74,7 @@ def lookup(kernel: str, workload: str, layout: str) -> Optional[dict]:
     if not os.path.exists(DATA):
         return None
     entry = json.load(open(DATA)).get(_key(kernel, workload, layout))
-    if entry is None or entry.get("revision") != source_revision():
+    if entry is None or entry.get("revision") != source_revision(kernel):
         return None
     return entry
 
@@ -110,7 +122,8 @@ def main():
     w_scale = COPY_KIB / _probe(write)
     agg = max if args.largest else statistics.median
     f_raw, w_raw = agg(_pick(fetch, args.kernel)), agg(_pick(write, args.kernel))
-    entry = {"revision": source_revision(), "fetch_raw": f_raw, "fetch_scale": round(f_scale, 4),
+    entry = {"revision": source_revision(args.kernel), "source": source_file(args.kernel),
+             "fetch_raw": f_raw, "fetch_scale": round(f_scale, 4),
              "write_raw": w_raw, "write_scale": round(w_scale, 4),
              "read_bytes": int(f_raw * f_scale * 1024), "written_bytes": int(w_raw * w_scale * 1024),
              "dispatches": len(_pick(fetch, args.kernel))}

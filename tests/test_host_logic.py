@@ -64,13 +64,21 @@ def test_traffic_store_scales_by_the_copy_probe_and_forgets_other_revisions(tmp_
     traffic.main()
     entry = traffic.lookup("apply_bf16_kernel", "w", "packed")
     assert entry["read_bytes"] == 1000 * 2 * 1024 and entry["written_bytes"] == 500 * 1024
-    assert entry["bytes"] == 2500 * 1024 and entry["revision"] == traffic.source_revision()
+    assert entry["bytes"] == 2500 * 1024 and entry["revision"] == traffic.source_revision("apply_bf16_kernel")
     assert traffic.lookup("apply_bf16_kernel", "other", "packed") is None
     # a reading taken on other kernel sources is not handed out
     data = json.load(open(traffic.DATA))
     data["apply_bf16_kernel|w|packed"]["revision"] = "0" * 16
     json.dump(data, open(traffic.DATA, "w"))
     assert traffic.lookup("apply_bf16_kernel", "w", "packed") is None
+    # a reading belongs to the file that defines the kernel (and the shared headers), so the
+    # long reuse kernel shares apply.hip's revision and the exact kernel has its own
+    assert traffic.source_file("apply_bf16_long_kernel") == "apply.hip"
+    assert traffic.source_file("exact_bf16_kernel") == "exact.hip"
+    assert traffic.source_revision("apply_bf16_long_kernel") == traffic.source_revision("apply_bf16_kernel")
+    assert traffic.source_revision("exact_bf16_kernel") != traffic.source_revision("apply_bf16_kernel")
+    with pytest.raises(ValueError):
+        traffic.source_file("nosuch_kernel")
 
 
 def test_query_stream_batches_differ_but_share_the_popularity_order():
