@@ -199,7 +199,10 @@ def run_resident(ac, synth, synthdb, traffic, args, cfg, *, extras=False):
         rec_extras["per_layer_mode"] = run_per_layer(ac, args, w, db, q, idx, score, ws, Q, K, V, O)
         if w.emb_dtype == "f16":
             rec_extras["projector"] = run_projector(ac, synth, args, w)
-        rec_extras["insert"] = run_insert(ac, args, w, Q, K, V)
+    if args.extras:   # database building at this workload's batch shape
+        ins = run_insert(ac, args, w, Q, K, V)
+        if ins is not None:
+            rec_extras["insert"] = ins
 
     # ----------------------------------------- the denominator: exact attention on every query
     O_exact = torch.zeros(B, L, Hq, S, D, dtype=dt, device=dev)
@@ -392,7 +395,8 @@ def run_insert(ac, args, w, Q, K, V):
     g = Hq // Hkv
     nbytes = (S * D * 2 * (2 + 2 / g) + tile * 2) * B * L * Hq
     return {"ms": ms, "tokens_per_s": B * S / (ms * 1e-3),
-            "roofline": {"kernel": "insert_bf16_kernel", "bound": "hbm",
+            "roofline": {"kernel": "insert_bf16_kernel" if S <= 128 else "insert_bf16_long_kernel",
+                         "bound": "hbm",
                          "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                          "algorithmic_bytes_per_launch": nbytes}}
@@ -588,7 +592,8 @@ def main():
                     help="which records to produce: 'all' (default) or a comma list of 2,3,4,index,host; "
                          "the headline workload is always included")
     ap.add_argument("--no-extras", dest="extras", action="store_false",
-                    help="skip per-layer mode, projector and database building on the headline workload")
+                    help="skip per-layer mode and projector (headline workload) and database building "
+                         "(every HBM-resident workload)")
     ap.add_argument("--entries", type=int, default=0, help="override the headline workload's map entries")
     ap.add_argument("--layout", choices=["packed", "dense"], default="packed",
                     help="storage layout of the map database (default: packed)")

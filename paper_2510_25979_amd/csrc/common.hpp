@@ -75,6 +75,14 @@ __host__ __device__ constexpr int v_piece_swizzle(int r) {
   return D == 128 ? 4 * (r & 3) : 4 * ((r >> 1) & 1);
 }
 
+// Permutation of the 16-byte pieces of a K row staged row-major and unpadded in LDS: piece p of
+// key row r sits at position p ^ k_piece_swizzle(r), so that the 16-byte operand reads of 32
+// consecutive rows spread over all banks (unchanged by r + 256 / (D / 8)).
+template <int D>
+__host__ __device__ constexpr int k_piece_swizzle(int r) {
+  return D == 128 ? (r & 15) : ((r >> 1) & 7);
+}
+
 // Stage V[j0 .. j0+nj)[0..D) (row-major, row stride D) into LDS transposed:
 // vt[d * kVtStride + j] = V[j0 + j][d].  All 256 threads take part.  Each task
 // moves a 4 (rows) x 8 (d) block: four 16-byte global loads, an in-register

@@ -69,12 +69,6 @@ __device__ __forceinline__ float max_with_other_half(float x) {
   return fmaxf(lo, hi);
 }
 
-// permutation of the 16-byte pieces of staged K row r (unchanged by r + 256 / (D / 8))
-template <int D>
-__host__ __device__ constexpr int k_piece_swizzle(int r) {
-  return D == 128 ? (r & 15) : ((r >> 1) & 7);
-}
-
 template <int D, bool CAUSAL, bool RESIDENT>
 __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel(const ExactArgs a) {
   constexpr int PPR = D / 8;                          // 16-byte pieces per row

@@ -13,8 +13,9 @@
 // with V (so O is exactly what the stored map yields, up to summation order).  Same transposed
 // products and register hand-over as the exact kernel: S^T = K Q^T (a lane holds 16 keys of one
 // query row), O^T = V^T A^T with A taken from the first product's result registers.
-// For S <= 128 K and V are staged in LDS once and both passes read them there; longer sequences
-// re-stage 128-key chunks in the second pass (L2 hits).
+// For S <= 128 K and V are staged in LDS once per group of query heads that share them and both
+// passes read them there; longer sequences have a kernel of their own that streams 64-key
+// chunks through two LDS stages (further down).
 //
 // Packed layout (see pack_maps_kernel): the result registers of one 32 x 32 score block map onto
 // packed 16 x 32 blocks directly -- register group q (4 registers) of lane (row i, half kh) is
@@ -74,8 +75,7 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_kernel(const InsertAr
   const size_t kv = (((size_t)b * a.Lc + l) * a.Hkv + kvh) * (size_t)S * D;
   const bf16_t* Kt = reinterpret_cast<const bf16_t*>(a.K) + kv;
   const bf16_t* Vt_src = reinterpret_cast<const bf16_t*>(a.V) + kv;
-  const int n_chunk = CAUSAL ? R + 1 : (S + kChunk - 1) / kChunk;
-  const int r0 = R * kChunk + 32 * wave;
+  const int r0 = R * kChunk + 32 * wave;   // R = 0: this kernel serves S <= 128, one key chunk
   const bool active = r0 < S;
   const int n32 = S >> 5;
   const size_t tile_elems = PACKED ? (size_t)packed_blocks(S, CAUSAL) * 512 : (size_t)S * S;
@@ -137,11 +137,11 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_kernel(const InsertAr
 
   // ---- pass 1: row maximum m (log2 domain, scale folded in) and row sum l of 2^(score - m)
   float m_run = -INFINITY, l_run = 0.f;
-  for (int c = 0; c < n_chunk; ++c) {
-    if (n_chunk > 1 || hl == 0) {   // a resident chunk (S <= 128) serves every head of the group
-      if (c > 0 || hl > 0) __syncthreads();
-      stage_k(c);
-      if (n_chunk == 1) stage_v(0);   // short sequences: V is staged once, next to K
+  {
+    constexpr int c = 0;
+    if (hl == 0) {   // the staged chunk serves every head of the group
+      stage_k(0);
+      stage_v(0);
       __syncthreads();
     }
     const int nblk = blocks(c);
@@ -178,13 +178,8 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_kernel(const InsertAr
     return reinterpret_cast<u32x2*>(At + (size_t)(r0 + il) * S + 32 * kb + 8 * q4 + 4 * kh);
   };
 
-  for (int c = 0; c < n_chunk; ++c) {
-    if (n_chunk > 1) {
-      __syncthreads();
-      stage_k(c);
-      stage_v(c);
-      __syncthreads();
-    }
+  {
+    constexpr int c = 0;
     const int nblk = blocks(c);
     for (int jb = 0; jb < nblk; ++jb) {
       f32x16 s = scores(c, jb);
@@ -234,6 +229,249 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_kernel(const InsertAr
   }   // heads of the group
 }
 
+// ------------------------------------------------------------------------------- S > 128
+// Long sequences: one workgroup = one (item, layer, query head, 128 query rows), walking the
+// keys in chunks of 64 -- twice, as above.  K and V reach the matrix cores the way they do in
+// the exact kernel: every chunk is copied global -> LDS directly (no data registers, no ALU
+// work) into one of two stages while the chunk before is multiplied, rows unpadded with the
+// 16-byte pieces permuted (k_piece_swizzle, v_piece_swizzle), V^T fetched with the
+// transposing LDS read.  The statistics pass needs no V and copies none.
+constexpr int kIChunk = 64;   // keys per staged chunk
+
+template <int D, bool CAUSAL, bool PACKED>
+__global__ __launch_bounds__(kThreads, 2) void insert_bf16_long_kernel(const InsertArgs a) {
+  constexpr int PPR = D / 8;                          // 16-byte pieces per row
+  constexpr int NCOPY = kIChunk * PPR / kWave / 4;    // copy instructions per wave, tensor, chunk
+  __shared__ __attribute__((aligned(16))) bf16_t kb0[kIChunk * D];
+  __shared__ __attribute__((aligned(16))) bf16_t vb0[kIChunk * D];
+  __shared__ __attribute__((aligned(16))) bf16_t kb1[kIChunk * D];
+  __shared__ __attribute__((aligned(16))) bf16_t vb1[kIChunk * D];
+  __shared__ __attribute__((aligned(16))) bf16_t ost_small[4 * 16 * kSmallOutStride];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int il = lane & 31, kh = lane >> 5;
+  const int S = a.S, g = a.Hq / a.Hkv;
+
+  // same id scheme as above with one head per workgroup: all row blocks of a head, and all
+  // heads that share K and V, get ids equal mod 8 (one XCD, one L2)
+  const int bid = blockIdx.x;
+  const int slot_id = bid >> 3;
+  const int grp = (slot_id / (g * a.n_rblk)) * 8 + (bid & 7);   // (item, layer, KV head)
+  const int hslot = (slot_id / a.n_rblk) % g;
+  const int R = a.n_rblk - 1 - slot_id % a.n_rblk;
+  if (grp >= a.n_tiles) return;
+  const int kvh = grp % a.Hkv;
+  const int l = (grp / a.Hkv) % a.Lc;
+  const int b = grp / (a.Hkv * a.Lc);
+  if (a.row_sel && a.row_sel[b] >= 0) return;
+  const int len = a.key_len ? min(max(a.key_len[b], 1), S) : S;
+  const int entry = a.slot ? a.slot[b] : -1;
+  const bool keep = entry >= 0 && entry < a.M;   // anything else: compute O only
+  const int h = kvh * g + hslot;
+
+  const size_t kv = (((size_t)b * a.Lc + l) * a.Hkv + kvh) * (size_t)S * D;
+  const bf16_t* Ksrc = reinterpret_cast<const bf16_t*>(a.K) + kv;
+  const bf16_t* Vsrc = reinterpret_cast<const bf16_t*>(a.V) + kv;
+  const size_t qo = (((size_t)b * a.Lc + l) * a.Hq + h) * (size_t)S * D;
+  const int n_all = (S + kIChunk - 1) / kIChunk;
+  const int n_chunk = CAUSAL ? min(2 * (R + 1), n_all) : n_all;   // the same for all four waves
+  const int r0 = R * kChunk + 32 * wave;
+  const bool active = r0 < S;
+  const int n32 = S >> 5;
+  const size_t tile_elems = PACKED ? (size_t)packed_blocks(S, CAUSAL) * 512 : (size_t)S * S;
+  bf16_t* At = reinterpret_cast<bf16_t*>(a.maps) +
+               (((size_t)(keep ? entry : 0) * a.L + (a.layer_begin + l)) * a.Hq + h) * tile_elems;
+
+  // ---- copies: instruction k = wave + 4 i fills LDS slots [64 k, 64 k + 64), slot = row * PPR +
+  // position; from one instruction to the next the row grows by 256 / PPR, which leaves both
+  // permutations unchanged.  Rows past the end of a ragged last chunk repeat its last row
+  // (finite, and never multiplied: the block count below stops before them).
+  const int slot0 = kWave * wave + lane;
+  const int crow = slot0 / PPR, cpos = slot0 % PPR;
+  const int kpiece = cpos ^ k_piece_swizzle<D>(crow);
+  const int vpiece = cpos ^ v_piece_swizzle<D>(crow);
+  auto prefetch = [&](bf16_t* kb, bf16_t* vb, int c, const bool WITH_V) {
+    const int nj = min(kIChunk, S - c * kIChunk);
+    const bf16_t* ksrc = Ksrc + (size_t)c * kIChunk * D;
+    const bf16_t* vsrc = Vsrc + (size_t)c * kIChunk * D;
+#pragma unroll
+    for (int i = 0; i < NCOPY; ++i) {
+      const int rr = min(crow + (256 / PPR) * i, nj - 1);
+      __builtin_amdgcn_global_load_lds(ksrc + (size_t)rr * D + 8 * kpiece,
+                                       kb + kWave * 8 * (wave + 4 * i), 16, 0, 0);
+      if (WITH_V)
+        __builtin_amdgcn_global_load_lds(vsrc + (size_t)rr * D + 8 * vpiece,
+                                         vb + kWave * 8 * (wave + 4 * i), 16, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // this wave's copies have landed (they are counted like loads), then everybody's; the
+  // barrier also retires the stage that the next copy overwrites
+  auto publish = [&]() {
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+  };
+
+  // ---- operand addresses (elements, relative to a stage), as in the exact kernel
+  int koff[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) koff[ks] = il * D + 8 * ((2 * ks + kh) ^ k_piece_swizzle<D>(il));
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  int voff[2][D / 32];
+  {
+    const int t = lane & 15;
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db) {
+        const int j = 4 * kh + 8 * half + (t >> 2);
+        const int d0 = 32 * db + 16 * (il >> 4) + 4 * (t & 3);
+        voff[half][db] = j * D + 8 * ((d0 >> 3) ^ v_piece_swizzle<D>(j)) + (d0 & 7);
+      }
+  }
+  // V^T operand of contraction step s2 of key block jb: slot e of lane half kh is key
+  // 16 s2 + 8 (e / 4) + 4 kh + e % 4 of the block, where the first product left the scores
+  auto vop = [&](const bf16_t* vb, int db, int jb, int s2) {
+    const int base = (32 * jb + 16 * s2) * D;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(vb + voff[0][db] + base));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(vb + voff[1][db] + base));
+    s16x8 w = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, w);
+  };
+
+  u32x4 q[D / 16];
+  if (active) {
+    const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.Q) + qo + (size_t)(r0 + il) * D + 8 * kh;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) q[ks] = *reinterpret_cast<const u32x4*>(qrow + 16 * ks);
+  }
+  // 32-key blocks of chunk c this wave's rows see
+  auto blocks = [&](int c) {
+    if (!active) return 0;
+    const int j0 = c * kIChunk;
+    int nblk = min(kIChunk, S - j0) >> 5;
+    if (CAUSAL) nblk = min(nblk, (r0 - j0) / 32 + 1);
+    return max(nblk, 0);
+  };
+  // scores^T of key block jb of the staged chunk c (keys beyond the diagonal or in the padding
+  // hidden; the first block of a row always has a visible key, so the running maximum is
+  // finite from then on)
+  auto scores = [&](const bf16_t* kb, int c, int jb) {
+    f32x16 s;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks)
+      s = mfma_bf16(*reinterpret_cast<const bf16x8*>(kb + koff[ks] + 32 * jb * D),
+                    __builtin_bit_cast(bf16x8, q[ks]), s);
+    const int j00 = c * kIChunk + 32 * jb;
+    if ((CAUSAL && j00 == r0) || j00 + 32 > len) {   // wave-uniform: most blocks skip the tests
+      int limit = len - 1 - j00;
+      if (CAUSAL) limit = min(limit, r0 + il - j00);
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (mfma_row(v, kh) > limit) s[v] = -INFINITY;
+    }
+    return s;
+  };
+
+  float m_run = -INFINITY, l_run = 0.f, inv_l = 0.f;
+  f32x16 acc[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+  // where register group q4 (scores 4 q4 .. 4 q4 + 3 of this lane) of 32-key block kb goes
+  const int r16 = (r0 >> 4) + (il >> 4);
+  auto map_piece = [&](int kb, int q4) -> u32x2* {
+    if (PACKED) {
+      const int blk = (CAUSAL ? packed_prefix(r16) : r16 * n32) + kb;
+      return reinterpret_cast<u32x2*>(At + (size_t)blk * 512 + (16 * q4 + (il & 15)) * 8 + 4 * kh);
+    }
+    return reinterpret_cast<u32x2*>(At + (size_t)(r0 + il) * S + 32 * kb + 8 * q4 + 4 * kh);
+  };
+
+  // one staged chunk.  First pass: row maximum m (log2 domain, scale folded in) and row sum l of
+  // 2^(score - m).  Second pass: normalised weights, rounded, stored, multiplied with V.
+  auto chunk = [&](const bf16_t* kb, const bf16_t* vb, int c, const bool SECOND)
+                   __attribute__((always_inline)) {
+    const int nblk = blocks(c);
+    for (int jb = 0; jb < nblk; ++jb) {
+      f32x16 s = scores(kb, c, jb);
+      if (!SECOND) {
+        float mx = s[0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx * a.scale_log2e);
+        float psum = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) psum += __builtin_amdgcn_exp2f(fmaf(s[v], a.scale_log2e, -m_new));
+        l_run = l_run * __builtin_amdgcn_exp2f(m_run - m_new) + psum;
+        m_run = m_new;
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          s[v] = __builtin_amdgcn_exp2f(fmaf(s[v], a.scale_log2e, -m_run)) * inv_l;
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          u32x4 pw;
+          pw.x = pack_bf16(s[8 * s2 + 0], s[8 * s2 + 1]);
+          pw.y = pack_bf16(s[8 * s2 + 2], s[8 * s2 + 3]);
+          pw.z = pack_bf16(s[8 * s2 + 4], s[8 * s2 + 5]);
+          pw.w = pack_bf16(s[8 * s2 + 6], s[8 * s2 + 7]);
+          if (keep) {
+            const int kb32 = 2 * c + jb;
+            *map_piece(kb32, 2 * s2) = u32x2{pw.x, pw.y};
+            *map_piece(kb32, 2 * s2 + 1) = u32x2{pw.z, pw.w};
+          }
+          const bf16x8 pop = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db) acc[db] = mfma_bf16(vop(vb, db, jb, s2), pop, acc[db]);
+        }
+      }
+    }
+  };
+  // all chunks of the row block, two per trip so that the stages are named statically (the
+  // compiler then knows that the copy in flight and the reads of the other stage do not meet)
+  auto pass = [&](const bool SECOND) __attribute__((always_inline)) {
+    prefetch(kb0, vb0, 0, SECOND);
+    publish();
+    int c = 0;
+    for (; c + 1 < n_chunk; c += 2) {
+      prefetch(kb1, vb1, c + 1, SECOND);
+      chunk(kb0, vb0, c, SECOND);
+      publish();
+      if (c + 2 < n_chunk) prefetch(kb0, vb0, c + 2, SECOND);
+      chunk(kb1, vb1, c + 1, SECOND);
+      publish();
+    }
+    if (c < n_chunk) {   // odd count: the last chunk sits in the first stage
+      chunk(kb0, vb0, c, SECOND);
+      publish();         // everybody is done with it before the next pass overwrites it
+    }
+  };
+
+  pass(false);
+  inv_l = 1.0f / (l_run + __shfl_xor(l_run, 32));
+  pass(true);
+
+  if (!active) return;
+  // A dense causal map carries its zeros: the 32-column blocks right of the diagonal block
+  // (the packed layout does not store them)
+  if (CAUSAL && !PACKED && keep) {
+    for (int kb = (r0 >> 5) + 1; kb < n32; ++kb)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) *map_piece(kb, q4) = u32x2{0u, 0u};
+  }
+  bf16_t* Oh = reinterpret_cast<bf16_t*>(a.O) + qo + (size_t)r0 * D;
+  store_tile_bf16_small<D>(acc, 1.0f, ost_small + wave * (16 * kSmallOutStride), Oh, lane);
+}
+
 // feature vector of item b into row slot[b] of the feature store (16-byte pieces)
 __global__ __launch_bounds__(kThreads) void insert_features_kernel(const u32x4* __restrict__ feat,
                                                                    u32x4* __restrict__ emb,
@@ -261,6 +499,21 @@ static hipError_t launch_insert_t(const InsertArgs& a, dim3 grid, hipStream_t st
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((insert_bf16_kernel<D, CAUSAL, PACKED>), grid, dim3(kThreads), lds, stream, a);
   return hipGetLastError();
+}
+
+template <int D, bool CAUSAL, bool PACKED>
+static hipError_t launch_insert_long_t(const InsertArgs& a, dim3 grid, hipStream_t stream) {
+  hipLaunchKernelGGL((insert_bf16_long_kernel<D, CAUSAL, PACKED>), grid, dim3(kThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_insert_long_d(const InsertArgs& a, dim3 grid, bool causal, bool packed,
+                                       hipStream_t stream) {
+  if (causal) return packed ? launch_insert_long_t<D, true, true>(a, grid, stream)
+                            : launch_insert_long_t<D, true, false>(a, grid, stream);
+  return packed ? launch_insert_long_t<D, false, true>(a, grid, stream)
+                : launch_insert_long_t<D, false, false>(a, grid, stream);
 }
 
 template <int D>
@@ -295,6 +548,9 @@ hipError_t launch_insert(const InsertLaunch& p, hipStream_t stream) {
   a.heads_per_wg = a.n_rblk == 1 ? g : 1;
   const int groups8 = (a.n_tiles + 7) / 8 * 8;   // padded to a multiple of 8
   const dim3 grid((unsigned)((size_t)groups8 * (g / a.heads_per_wg) * a.n_rblk));
+  if (a.n_rblk > 1)   // S > 128
+    return p.D == 64 ? launch_insert_long_d<64>(a, grid, p.causal, p.packed, stream)
+                     : launch_insert_long_d<128>(a, grid, p.causal, p.packed, stream);
   return p.D == 64 ? launch_insert_d<64>(a, grid, p.causal, p.packed, stream)
                    : launch_insert_d<128>(a, grid, p.causal, p.packed, stream);
 }

@@ -558,6 +558,8 @@ INSERT_CASES = [
     (2, 1, 2, 2, 96, 128, True),
     (2, 1, 2, 1, 288, 64, True),      # three key chunks, ragged last row block
     (2, 1, 2, 2, 160, 128, False),    # dense maps, ragged last chunk
+    (2, 1, 2, 1, 512, 128, True),     # four row blocks, up to eight 64-key chunks, shared K and V
+    (2, 2, 2, 2, 352, 64, False),     # dense maps, 32 keys in the last chunk, one wave in the last row block
 ]
 
 
