@@ -29,7 +29,8 @@ struct SearchArgs {
   const int32_t* map_of;
   int32_t N, E, B, k, metric;
   int32_t q0, nq;          // query super-block handled by this launch (phase 1)
-  int32_t rows_per_wg, G;  // group size and count
+  int32_t rows_per_wg, G;  // group size and count (a group: the rows one partial result covers)
+  int32_t wg_rows;         // rows one phase-1 workgroup scans: the group, or four groups of 32
   float threshold;
   float* part_s;           // [B][G]
   int32_t* part_i;         // [B][G]
@@ -93,8 +94,8 @@ __global__ __launch_bounds__(kThreads) void search_f16_kernel(const SearchArgs a
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) { best_s[qb] = -INFINITY; best_i[qb] = kIdxNone; }
 
-  const int row_begin = blockIdx.x * a.rows_per_wg;
-  const int row_end = min(row_begin + a.rows_per_wg, a.N);
+  const int row_begin = blockIdx.x * a.wg_rows;
+  const int row_end = min(row_begin + a.wg_rows, a.N);
   const f16_t* emb = reinterpret_cast<const f16_t*>(a.emb);
   for (int rb = row_begin + 32 * wave; rb < row_end; rb += 128) {
     // database operand: lane (il, kh) holds emb[rb + il][16 ks + 8 kh .. +8); rows past the
@@ -124,12 +125,33 @@ __global__ __launch_bounds__(kThreads) void search_f16_kernel(const SearchArgs a
       }
     }
   }
-  // combine the two lane halves, then the four waves
+  // combine the two lane halves
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
     const float so = __shfl_xor(best_s[qb], 32);
     const int io = __shfl_xor(best_i[qb], 32);
     if (ranks_before(so, io, best_s[qb], best_i[qb])) { best_s[qb] = so; best_i[qb] = io; }
+  }
+  if (a.rows_per_wg == 32) {
+    // groups of 32 rows (top-k searches: the finalising kernel re-scores k whole groups per
+    // query, so small groups are cheap): a workgroup scans 128 rows in one pass and every
+    // wave's 32 rows are a group of their own -- nothing to merge
+    const int gi = 4 * blockIdx.x + wave;
+    if (kh == 0 && gi < a.G) {
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        const int t = 32 * qb + il;
+        if (t < a.nq) {
+          a.part_s[(size_t)(a.q0 + t) * a.G + gi] = best_s[qb];
+          a.part_i[(size_t)(a.q0 + t) * a.G + gi] = best_i[qb];
+        }
+      }
+    }
+    return;
+  }
+  // one group per workgroup: the four waves meet in LDS
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
     if (kh == 0) {
       red_s[wave * 32 * NQB + 32 * qb + il] = best_s[qb];
       red_i[wave * 32 * NQB + 32 * qb + il] = best_i[qb];
@@ -548,9 +570,18 @@ enum { kModeValu = 0, kModeMfma = 1, kModeMfmaBig = 2 };
 constexpr int kBigBatch = 64;   // above this many queries the query-stationary kernel is used
 constexpr int kBigRowsMin = 50000;   // and from this many database rows on, whatever the batch
 
-static void search_plan(int32_t N, int32_t mode, int32_t k, int32_t* rows_per_wg, int32_t* G) {
+static void search_plan(int32_t N, int32_t mode, int32_t k, int32_t* rows_per_wg, int32_t* G,
+                        int32_t* wg_rows = nullptr) {
   int rpw;
-  if (mode == kModeMfma) {
+  int scan = 0;   // rows per phase-1 workgroup when that is not the group
+  if (mode == kModeMfma && k > 1 && N <= 32 * 1024) {
+    // top-k: the second phase re-scores k whole groups per query on the vector ALUs, so the
+    // groups are as small as the first phase can make them: the 32 rows of one wave.  Beyond
+    // about a thousand groups the k selection rounds over the group maxima cost more than the
+    // smaller groups save (140,000 rows, k = 4: 36 against 28 us).
+    rpw = 32;
+    scan = 128;
+  } else if (mode == kModeMfma) {
     // 128 rows per pass of a workgroup; more passes per workgroup for large databases so that
     // the query tile staged in LDS is amortised, while keeping >= ~1000 workgroups
     long c = ((long)N + 128L * 1024 - 1) / (128L * 1024);
@@ -571,6 +602,7 @@ static void search_plan(int32_t N, int32_t mode, int32_t k, int32_t* rows_per_wg
   }
   *rows_per_wg = rpw;
   *G = (N + rpw - 1) / rpw;
+  if (wg_rows) *wg_rows = scan ? scan : rpw;
 }
 
 static bool use_mfma(int32_t is_f16, int32_t metric, int32_t E) {
@@ -637,7 +669,7 @@ hipError_t launch_search(const SearchLaunch& p, hipStream_t stream) {
   a.idx = p.idx; a.score = p.score; a.hit = p.hit;
   const int mode = search_mode(p.is_f16, p.metric, p.E, p.B, p.N);
   const bool mfma = mode == kModeMfma;
-  search_plan(p.N, mode, p.k, &a.rows_per_wg, &a.G);
+  search_plan(p.N, mode, p.k, &a.rows_per_wg, &a.G, &a.wg_rows);
   unsigned char* ws = reinterpret_cast<unsigned char*>(p.ws);
   size_t part_bytes = ((size_t)p.B * a.G * 8 + 255) / 256 * 256;
   a.part_s = reinterpret_cast<float*>(ws);
@@ -672,7 +704,7 @@ hipError_t launch_search(const SearchLaunch& p, hipStream_t stream) {
       int nqb = 1;
       while (32 * nqb < a.nq) nqb <<= 1;
       const size_t lds = f16_lds_bytes(nqb, p.E);
-      const dim3 grid((unsigned)a.G);
+      const dim3 grid((unsigned)((p.N + a.wg_rows - 1) / a.wg_rows));
       hipError_t e;
       if (ksmax == 8) e = launch_f16_phase1<8>(a, nqb, grid, lds, stream);
       else if (ksmax == 16) e = launch_f16_phase1<16>(a, nqb, grid, lds, stream);

@@ -279,6 +279,9 @@ SEARCH_CASES = [
     (50021, 256, 5, 1, torch.float16, "ip", True),      # large database, a handful of queries
     (60000, 128, 33, 3, torch.float16, "ip", True),     # large database, one query past a block
     (50000, 512, 1, 1, torch.float16, "ip", True),      # large database, a single query
+    (32768, 128, 9, 5, torch.float16, "ip", True),      # top-k, the most 32-row groups (1,024)
+    (40000, 256, 10, 3, torch.float16, "ip", True),     # top-k just above that: one group per workgroup
+    (2021, 64, 70, 6, torch.float16, "ip", True),       # top-k, ragged last group, three query blocks
 ]
 
 
