@@ -195,12 +195,12 @@ def run_resident(ac, synth, synthdb, traffic, args, cfg, *, extras=False):
         del O_eager, graph
 
     rec_extras = {}
-    if extras and args.extras:
+    if extras and "per_layer" in args.extras:
         rec_extras["per_layer_mode"] = run_per_layer(ac, args, w, db, q, idx, score, ws, Q, K, V, O)
-        if w.emb_dtype == "f16":
-            rec_extras["projector"] = run_projector(ac, synth, args, w)
-    if args.extras:   # database building at this workload's batch shape
-        ins = run_insert(ac, args, w, Q, K, V)
+    if extras and "projector" in args.extras and w.emb_dtype == "f16":
+        rec_extras["projector"] = run_projector(ac, synth, args, w)
+    if "insert" in args.extras:   # database building at this workload's batch shape
+        ins = run_insert(ac, args, traffic, w, Q, K, V)
         if ins is not None:
             rec_extras["insert"] = ins
 
@@ -373,7 +373,7 @@ def run_projector(ac, synth, args, w):
                                  f"the two layers add {flops / 1e9:.2f} GFLOP on the fp32 matrix cores"}}
 
 
-def run_insert(ac, args, w, Q, K, V):
+def run_insert(ac, args, traffic, w, Q, K, V):
     """Database building on the device (Fig. 3, steps 2-3): the whole batch is computed and
     remembered (maps written in the packed layout)."""
     dev = Q.device
@@ -394,9 +394,11 @@ def run_insert(ac, args, w, Q, K, V):
     dbi.close()
     g = Hq // Hkv
     nbytes = (S * D * 2 * (2 + 2 / g) + tile * 2) * B * L * Hq
+    kernel = "insert_bf16_kernel"
+    reading = traffic.lookup(kernel, w.name, "packed") if not args.entries else None
     return {"ms": ms, "tokens_per_s": B * S / (ms * 1e-3),
-            "roofline": {"kernel": "insert_bf16_kernel" if S <= 128 else "insert_bf16_long_kernel",
-                         "bound": "hbm",
+            "roofline": {"kernel": kernel, "bound": "hbm",
+                         "traffic": reading["bytes"] if reading else None,
                          "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                          "algorithmic_bytes_per_launch": nbytes}}
@@ -591,9 +593,11 @@ def main():
     ap.add_argument("--workloads", default="all",
                     help="which records to produce: 'all' (default) or a comma list of 2,3,4,index,host; "
                          "the headline workload is always included")
-    ap.add_argument("--no-extras", dest="extras", action="store_false",
-                    help="skip per-layer mode and projector (headline workload) and database building "
-                         "(every HBM-resident workload)")
+    ap.add_argument("--extras", default="per_layer,projector,insert",
+                    help="what to measure besides the step: per_layer and projector (headline "
+                         "workload), insert = database building (every HBM-resident workload)")
+    ap.add_argument("--no-extras", dest="extras", action="store_const", const="",
+                    help="the same as --extras ''")
     ap.add_argument("--entries", type=int, default=0, help="override the headline workload's map entries")
     ap.add_argument("--layout", choices=["packed", "dense"], default="packed",
                     help="storage layout of the map database (default: packed)")
@@ -605,6 +609,10 @@ def main():
                     help="also launch one plain 1 GiB device copy per workload (a kernel of known HBM "
                          "traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled)")
     args = ap.parse_args()
+    args.extras = {x for x in args.extras.split(",") if x}
+    unknown = args.extras - {"per_layer", "projector", "insert"}
+    if unknown:
+        ap.error(f"unknown --extras entries: {sorted(unknown)}")
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
               "use --gpus 1", file=sys.stderr)

@@ -14,8 +14,8 @@
 // products and register hand-over as the exact kernel: S^T = K Q^T (a lane holds 16 keys of one
 // query row), O^T = V^T A^T with A taken from the first product's result registers.
 // For S <= 128 K and V are staged in LDS once per group of query heads that share them and both
-// passes read them there; longer sequences have a kernel of their own that streams 64-key
-// chunks through two LDS stages (further down).
+// passes of every head read them there; longer sequences stream 64-key chunks through two LDS
+// stages, once per pass.
 //
 // Packed layout (see pack_maps_kernel): the result registers of one 32 x 32 score block map onto
 // packed 16 x 32 blocks directly -- register group q (4 registers) of lane (row i, half kh) is
@@ -25,8 +25,6 @@
 #include "launch.hpp"
 
 namespace ac {
-
-constexpr int kKPadI = 8;   // elements of padding per staged K row
 
 struct InsertArgs {
   const void *Q, *K, *V;
@@ -38,208 +36,20 @@ struct InsertArgs {
   float scale_log2e;
 };
 
-template <int D, bool CAUSAL, bool PACKED>
-__global__ __launch_bounds__(kThreads, 2) void insert_bf16_kernel(const InsertArgs a) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int KS = D + kKPadI;
-  bf16_t* ks_lds = reinterpret_cast<bf16_t*>(smem);   // [128][KS]
-  bf16_t* vt = ks_lds + kChunk * KS;                  // [D][kVtStride]
-  bf16_t* ost_small = vt + D * kVtStride;             // [4][16][kSmallOutStride]: results on their way out
-
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int il = lane & 31, kh = lane >> 5;
-  const int S = a.S, g = a.Hq / a.Hkv;
-
-  // Workgroup ids that are equal mod 8 run on the same XCD and share its L2.  All row blocks of
-  // one (item, layer, head) AND all g heads that read the same K and V get such ids, so K and
-  // V come from HBM once per group.  For S <= 128 one workgroup walks all g heads of the group
-  // itself (heads_per_wg = g): K and V are staged -- and V is transposed -- once per group
-  // instead of once per query head.
-  const int bid = blockIdx.x;
-  const int hslots = g / a.heads_per_wg;
-  const int slot_id = bid >> 3;
-  const int grp = (slot_id / (hslots * a.n_rblk)) * 8 + (bid & 7);   // (item, layer, KV head)
-  const int hslot = (slot_id / a.n_rblk) % hslots;
-  const int R = a.n_rblk - 1 - slot_id % a.n_rblk;
-  if (grp >= a.n_tiles) return;
-  const int kvh = grp % a.Hkv;
-  const int l = (grp / a.Hkv) % a.Lc;
-  const int b = grp / (a.Hkv * a.Lc);
-  if (a.row_sel && a.row_sel[b] >= 0) return;
-  // real tokens of this sentence in a right-padded batch: later keys get weight zero
-  const int len = a.key_len ? min(max(a.key_len[b], 1), S) : S;
-  const int entry = a.slot ? a.slot[b] : -1;
-  const bool keep = entry >= 0 && entry < a.M;   // anything else: compute O only
-
-  const size_t kv = (((size_t)b * a.Lc + l) * a.Hkv + kvh) * (size_t)S * D;
-  const bf16_t* Kt = reinterpret_cast<const bf16_t*>(a.K) + kv;
-  const bf16_t* Vt_src = reinterpret_cast<const bf16_t*>(a.V) + kv;
-  const int r0 = R * kChunk + 32 * wave;   // R = 0: this kernel serves S <= 128, one key chunk
-  const bool active = r0 < S;
-  const int n32 = S >> 5;
-  const size_t tile_elems = PACKED ? (size_t)packed_blocks(S, CAUSAL) * 512 : (size_t)S * S;
-  u32x4 q[D / 16];
-  bf16_t* At = nullptr;   // this head's map in the store, set per head
-
-  auto stage_k = [&](int c) {
-    const int j0 = c * kChunk, nj = min(kChunk, S - j0);
-    constexpr int DQ = D / 8;
-    const u32x4* src = reinterpret_cast<const u32x4*>(Kt + (size_t)j0 * D);
-    for (int p = tid; p < nj * DQ; p += kThreads) {
-      const int j = p / DQ, dq = p % DQ;
-      *reinterpret_cast<u32x4*>(ks_lds + j * KS + 8 * dq) = src[p];
-    }
-  };
-  auto stage_v = [&](int c) {
-    const int j0 = c * kChunk;
-    stage_v_transposed<D>(Vt_src + (size_t)j0 * D, min(kChunk, S - j0), vt, tid);
-  };
-  // 32-key blocks of chunk c this wave's rows see
-  auto blocks = [&](int c) {
-    if (!active) return 0;
-    const int j0 = c * kChunk;
-    int nblk = min(kChunk, S - j0) >> 5;
-    if (CAUSAL) nblk = min(nblk, (r0 - j0) / 32 + 1);
-    return max(nblk, 0);
-  };
-  // scores^T of key block jb of the staged chunk (keys beyond the diagonal or in the padding
-  // hidden; block 0 always has a visible key, so the running maximum is finite from then on)
-  auto scores = [&](int c, int jb) {
-    f32x16 s;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) s[v] = 0.f;
-    const bf16_t* krow = ks_lds + (32 * jb + il) * KS + 8 * kh;
-#pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks)
-      s = mfma_bf16(*reinterpret_cast<const bf16x8*>(krow + 16 * ks), __builtin_bit_cast(bf16x8, q[ks]), s);
-    const int j00 = c * kChunk + 32 * jb;
-    if ((CAUSAL && j00 == r0) || j00 + 32 > len) {   // wave-uniform: most blocks skip the tests
-      int limit = len - 1 - j00;
-      if (CAUSAL) limit = min(limit, r0 + il - j00);
-#pragma unroll
-      for (int v = 0; v < 16; ++v)
-        if (mfma_row(v, kh) > limit) s[v] = -INFINITY;
-    }
-    return s;
-  };
-
-  for (int hl = 0; hl < a.heads_per_wg; ++hl) {
-  const int h = kvh * g + hslot * a.heads_per_wg + hl;
-  const size_t qo = (((size_t)b * a.Lc + l) * a.Hq + h) * (size_t)S * D;
-  At = reinterpret_cast<bf16_t*>(a.maps) +
-       (((size_t)(keep ? entry : 0) * a.L + (a.layer_begin + l)) * a.Hq + h) * tile_elems;
-  if (active) {
-    const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.Q) + qo + (size_t)(r0 + il) * D + 8 * kh;
-#pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) q[ks] = *reinterpret_cast<const u32x4*>(qrow + 16 * ks);
-  }
-
-  // ---- pass 1: row maximum m (log2 domain, scale folded in) and row sum l of 2^(score - m)
-  float m_run = -INFINITY, l_run = 0.f;
-  {
-    constexpr int c = 0;
-    if (hl == 0) {   // the staged chunk serves every head of the group
-      stage_k(0);
-      stage_v(0);
-      __syncthreads();
-    }
-    const int nblk = blocks(c);
-    for (int jb = 0; jb < nblk; ++jb) {
-      const f32x16 s = scores(c, jb);
-      float mx = s[0];
-#pragma unroll
-      for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run, mx * a.scale_log2e);
-      float psum = 0.f;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) psum += __builtin_amdgcn_exp2f(fmaf(s[v], a.scale_log2e, -m_new));
-      l_run = l_run * __builtin_amdgcn_exp2f(m_run - m_new) + psum;
-      m_run = m_new;
-    }
-  }
-  const float inv_l = 1.0f / (l_run + __shfl_xor(l_run, 32));
-
-  // ---- pass 2: normalised weights, rounded, stored, multiplied with V
-  f32x16 acc[D / 32];
-#pragma unroll
-  for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
-
-  // where register group q4 (scores 4 q4 .. 4 q4 + 3 of this lane) of key block kb goes
-  const int r16 = (r0 >> 4) + (il >> 4);
-  auto map_piece = [&](int kb, int q4) -> u32x2* {
-    if (PACKED) {
-      const int blk = (CAUSAL ? packed_prefix(r16) : r16 * n32) + kb;
-      return reinterpret_cast<u32x2*>(At + (size_t)blk * 512 + (16 * q4 + (il & 15)) * 8 + 4 * kh);
-    }
-    return reinterpret_cast<u32x2*>(At + (size_t)(r0 + il) * S + 32 * kb + 8 * q4 + 4 * kh);
-  };
-
-  {
-    constexpr int c = 0;
-    const int nblk = blocks(c);
-    for (int jb = 0; jb < nblk; ++jb) {
-      f32x16 s = scores(c, jb);
-#pragma unroll
-      for (int v = 0; v < 16; ++v)
-        s[v] = __builtin_amdgcn_exp2f(fmaf(s[v], a.scale_log2e, -m_run)) * inv_l;
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        u32x4 pw;
-        pw.x = pack_bf16(s[8 * s2 + 0], s[8 * s2 + 1]);
-        pw.y = pack_bf16(s[8 * s2 + 2], s[8 * s2 + 3]);
-        pw.z = pack_bf16(s[8 * s2 + 4], s[8 * s2 + 5]);
-        pw.w = pack_bf16(s[8 * s2 + 6], s[8 * s2 + 7]);
-        if (keep) {
-          const int kb = 4 * c + jb;
-          *map_piece(kb, 2 * s2) = u32x2{pw.x, pw.y};
-          *map_piece(kb, 2 * s2 + 1) = u32x2{pw.z, pw.w};
-        }
-        const bf16x8 pop = __builtin_bit_cast(bf16x8, pw);
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db) {
-          const bf16_t* vrow = vt + (32 * db + il) * kVtStride + 32 * jb + 16 * s2 + 4 * kh;
-          u32x2 lo = *reinterpret_cast<const u32x2*>(vrow);
-          u32x2 hi = *reinterpret_cast<const u32x2*>(vrow + 8);
-          u32x4 w = {lo.x, lo.y, hi.x, hi.y};
-          acc[db] = mfma_bf16(__builtin_bit_cast(bf16x8, w), pop, acc[db]);
-        }
-      }
-    }
-  }
-  // A dense causal map carries its zeros: the 32-column blocks right of the diagonal block
-  // (the packed layout does not store them)
-  if (CAUSAL && !PACKED && keep && active) {
-    for (int kb = (r0 >> 5) + 1; kb < n32; ++kb)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) *map_piece(kb, q4) = u32x2{0u, 0u};
-  }
-
-  bf16_t* Oh = reinterpret_cast<bf16_t*>(a.O) + qo + (size_t)r0 * D;
-  if (a.heads_per_wg > 1) {
-    // K and V stay staged for the next head: the result leaves through the wave's small buffer
-    if (active) store_tile_bf16_small<D>(acc, 1.0f, ost_small + wave * (16 * kSmallOutStride), Oh, lane);
-  } else {
-    __syncthreads();   // one head per workgroup: K is dead, the whole tile is staged on top of it
-    if (active) store_tile_bf16<D>(acc, 1.0f, ks_lds + wave * (32 * (D + 4)), Oh, lane);
-  }
-  }   // heads of the group
-}
-
-// ------------------------------------------------------------------------------- S > 128
-// Long sequences: one workgroup = one (item, layer, query head, 128 query rows), walking the
-// keys in chunks of 64 -- twice, as above.  K and V reach the matrix cores the way they do in
-// the exact kernel: every chunk is copied global -> LDS directly (no data registers, no ALU
-// work) into one of two stages while the chunk before is multiplied, rows unpadded with the
-// 16-byte pieces permuted (k_piece_swizzle, v_piece_swizzle), V^T fetched with the
-// transposing LDS read.  The statistics pass needs no V and copies none.
+// One workgroup = one (item, layer, group of query heads that share K and V, 128 query rows),
+// walking the keys in chunks of 64 -- twice per head, see above.  K and V reach the matrix cores
+// the way they do in the exact kernel: every chunk is copied global -> LDS directly (no data
+// registers, no ALU work) into one of two stages, rows unpadded with the 16-byte pieces
+// permuted (k_piece_swizzle, v_piece_swizzle), V^T fetched with the transposing LDS read.
+//   RESIDENT (S <= 128): both chunks sit in the two stages for the whole tile and the workgroup
+//   walks all g query heads of the group -- K and V come from HBM once per group, and after the
+//   one barrier behind the copy the four waves never meet again.
+//   Streaming (S > 128): one head per workgroup; the copy of chunk c + 1 is in flight while chunk
+//   c is multiplied, one barrier per chunk; the statistics pass needs no V and copies none.
 constexpr int kIChunk = 64;   // keys per staged chunk
 
-template <int D, bool CAUSAL, bool PACKED>
-__global__ __launch_bounds__(kThreads, 2) void insert_bf16_long_kernel(const InsertArgs a) {
+template <int D, bool CAUSAL, bool PACKED, bool RESIDENT>
+__global__ __launch_bounds__(kThreads, 2) void insert_bf16_kernel(const InsertArgs a) {
   constexpr int PPR = D / 8;                          // 16-byte pieces per row
   constexpr int NCOPY = kIChunk * PPR / kWave / 4;    // copy instructions per wave, tensor, chunk
   __shared__ __attribute__((aligned(16))) bf16_t kb0[kIChunk * D];
@@ -253,12 +63,16 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_long_kernel(const Ins
   const int il = lane & 31, kh = lane >> 5;
   const int S = a.S, g = a.Hq / a.Hkv;
 
-  // same id scheme as above with one head per workgroup: all row blocks of a head, and all
-  // heads that share K and V, get ids equal mod 8 (one XCD, one L2)
+  // same id scheme as above: all row blocks of a head, and all heads that share K and V, get
+  // ids equal mod 8 (one XCD, one L2).  RESIDENT (S <= 128): both chunks of K and V sit in the
+  // two stages for the whole tile and the workgroup walks all heads_per_wg = g query heads
+  // that share them; between the one barrier after the copy and the end of the tile the four
+  // waves never meet again.
   const int bid = blockIdx.x;
+  const int hslots = g / a.heads_per_wg;
   const int slot_id = bid >> 3;
-  const int grp = (slot_id / (g * a.n_rblk)) * 8 + (bid & 7);   // (item, layer, KV head)
-  const int hslot = (slot_id / a.n_rblk) % g;
+  const int grp = (slot_id / (hslots * a.n_rblk)) * 8 + (bid & 7);   // (item, layer, KV head)
+  const int hslot = (slot_id / a.n_rblk) % hslots;
   const int R = a.n_rblk - 1 - slot_id % a.n_rblk;
   if (grp >= a.n_tiles) return;
   const int kvh = grp % a.Hkv;
@@ -268,20 +82,17 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_long_kernel(const Ins
   const int len = a.key_len ? min(max(a.key_len[b], 1), S) : S;
   const int entry = a.slot ? a.slot[b] : -1;
   const bool keep = entry >= 0 && entry < a.M;   // anything else: compute O only
-  const int h = kvh * g + hslot;
 
   const size_t kv = (((size_t)b * a.Lc + l) * a.Hkv + kvh) * (size_t)S * D;
   const bf16_t* Ksrc = reinterpret_cast<const bf16_t*>(a.K) + kv;
   const bf16_t* Vsrc = reinterpret_cast<const bf16_t*>(a.V) + kv;
-  const size_t qo = (((size_t)b * a.Lc + l) * a.Hq + h) * (size_t)S * D;
   const int n_all = (S + kIChunk - 1) / kIChunk;
   const int n_chunk = CAUSAL ? min(2 * (R + 1), n_all) : n_all;   // the same for all four waves
   const int r0 = R * kChunk + 32 * wave;
   const bool active = r0 < S;
   const int n32 = S >> 5;
   const size_t tile_elems = PACKED ? (size_t)packed_blocks(S, CAUSAL) * 512 : (size_t)S * S;
-  bf16_t* At = reinterpret_cast<bf16_t*>(a.maps) +
-               (((size_t)(keep ? entry : 0) * a.L + (a.layer_begin + l)) * a.Hq + h) * tile_elems;
+  bf16_t* At = nullptr;   // the current head's map in the store
 
   // ---- copies: instruction k = wave + 4 i fills LDS slots [64 k, 64 k + 64), slot = row * PPR +
   // position; from one instruction to the next the row grows by 256 / PPR, which leaves both
@@ -344,11 +155,6 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_long_kernel(const Ins
   };
 
   u32x4 q[D / 16];
-  if (active) {
-    const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.Q) + qo + (size_t)(r0 + il) * D + 8 * kh;
-#pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) q[ks] = *reinterpret_cast<const u32x4*>(qrow + 16 * ks);
-  }
   // 32-key blocks of chunk c this wave's rows see
   auto blocks = [&](int c) {
     if (!active) return 0;
@@ -381,10 +187,6 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_long_kernel(const Ins
 
   float m_run = -INFINITY, l_run = 0.f, inv_l = 0.f;
   f32x16 acc[D / 32];
-#pragma unroll
-  for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
   // where register group q4 (scores 4 q4 .. 4 q4 + 3 of this lane) of 32-key block kb goes
   const int r16 = (r0 >> 4) + (il >> 4);
   auto map_piece = [&](int kb, int q4) -> u32x2* {
@@ -456,20 +258,54 @@ __global__ __launch_bounds__(kThreads, 2) void insert_bf16_long_kernel(const Ins
     }
   };
 
-  pass(false);
-  inv_l = 1.0f / (l_run + __shfl_xor(l_run, 32));
-  pass(true);
-
-  if (!active) return;
-  // A dense causal map carries its zeros: the 32-column blocks right of the diagonal block
-  // (the packed layout does not store them)
-  if (CAUSAL && !PACKED && keep) {
-    for (int kb = (r0 >> 5) + 1; kb < n32; ++kb)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) *map_piece(kb, q4) = u32x2{0u, 0u};
+  if (RESIDENT) {
+    prefetch(kb0, vb0, 0, true);
+    if (n_chunk > 1) prefetch(kb1, vb1, 1, true);
+    publish();
   }
-  bf16_t* Oh = reinterpret_cast<bf16_t*>(a.O) + qo + (size_t)r0 * D;
-  store_tile_bf16_small<D>(acc, 1.0f, ost_small + wave * (16 * kSmallOutStride), Oh, lane);
+  const int n_heads = RESIDENT ? a.heads_per_wg : 1;   // streaming: one head per workgroup
+  for (int hl = 0; hl < n_heads; ++hl) {
+    const int h = kvh * g + hslot * a.heads_per_wg + hl;
+    const size_t qo = (((size_t)b * a.Lc + l) * a.Hq + h) * (size_t)S * D;
+    At = reinterpret_cast<bf16_t*>(a.maps) +
+         (((size_t)(keep ? entry : 0) * a.L + (a.layer_begin + l)) * a.Hq + h) * tile_elems;
+    if (active) {
+      const bf16_t* qrow = reinterpret_cast<const bf16_t*>(a.Q) + qo + (size_t)(r0 + il) * D + 8 * kh;
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) q[ks] = *reinterpret_cast<const u32x4*>(qrow + 16 * ks);
+    }
+    m_run = -INFINITY;
+    l_run = 0.f;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+
+    if (RESIDENT) {
+      chunk(kb0, vb0, 0, false);
+      if (n_chunk > 1) chunk(kb1, vb1, 1, false);
+      inv_l = 1.0f / (l_run + __shfl_xor(l_run, 32));
+      chunk(kb0, vb0, 0, true);
+      if (n_chunk > 1) chunk(kb1, vb1, 1, true);
+    } else {
+      pass(false);
+      inv_l = 1.0f / (l_run + __shfl_xor(l_run, 32));
+      pass(true);
+    }
+
+    if (active) {
+      // A dense causal map carries its zeros: the 32-column blocks right of the diagonal block
+      // (the packed layout does not store them)
+      if (CAUSAL && !PACKED && keep) {
+        for (int kb = (r0 >> 5) + 1; kb < n32; ++kb)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) *map_piece(kb, q4) = u32x2{0u, 0u};
+      }
+      // the result leaves through the wave's small buffer: K and V stay where they are
+      bf16_t* Oh = reinterpret_cast<bf16_t*>(a.O) + qo + (size_t)r0 * D;
+      store_tile_bf16_small<D>(acc, 1.0f, ost_small + wave * (16 * kSmallOutStride), Oh, lane);
+    }
+  }
 }
 
 // feature vector of item b into row slot[b] of the feature store (16-byte pieces)
@@ -486,39 +322,18 @@ __global__ __launch_bounds__(kThreads) void insert_features_kernel(const u32x4* 
     emb[(size_t)entry * pieces + p] = feat[(size_t)b * pieces + p];
 }
 
-// the small output buffers exist only when a workgroup walks several heads
-static size_t insert_lds_bytes(int D, int heads_per_wg) {
-  return (size_t)(kChunk * (D + kKPadI) + D * kVtStride +
-                  (heads_per_wg > 1 ? 4 * 16 * kSmallOutStride : 0)) * sizeof(bf16_t);
-}
-
 template <int D, bool CAUSAL, bool PACKED>
 static hipError_t launch_insert_t(const InsertArgs& a, dim3 grid, hipStream_t stream) {
-  const size_t lds = insert_lds_bytes(D, a.heads_per_wg);
-  hipError_t e = ensure_lds<&insert_bf16_kernel<D, CAUSAL, PACKED>>(lds);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((insert_bf16_kernel<D, CAUSAL, PACKED>), grid, dim3(kThreads), lds, stream, a);
+  if (a.n_rblk == 1)
+    hipLaunchKernelGGL((insert_bf16_kernel<D, CAUSAL, PACKED, true>), grid, dim3(kThreads), 0, stream, a);
+  else
+    hipLaunchKernelGGL((insert_bf16_kernel<D, CAUSAL, PACKED, false>), grid, dim3(kThreads), 0, stream, a);
   return hipGetLastError();
-}
-
-template <int D, bool CAUSAL, bool PACKED>
-static hipError_t launch_insert_long_t(const InsertArgs& a, dim3 grid, hipStream_t stream) {
-  hipLaunchKernelGGL((insert_bf16_long_kernel<D, CAUSAL, PACKED>), grid, dim3(kThreads), 0, stream, a);
-  return hipGetLastError();
-}
-
-template <int D>
-static hipError_t launch_insert_long_d(const InsertArgs& a, dim3 grid, bool causal, bool packed,
-                                       hipStream_t stream) {
-  if (causal) return packed ? launch_insert_long_t<D, true, true>(a, grid, stream)
-                            : launch_insert_long_t<D, true, false>(a, grid, stream);
-  return packed ? launch_insert_long_t<D, false, true>(a, grid, stream)
-                : launch_insert_long_t<D, false, false>(a, grid, stream);
 }
 
 template <int D>
 static hipError_t launch_insert_d(const InsertArgs& a, dim3 grid, bool causal, bool packed,
-                                  hipStream_t stream) {
+                                       hipStream_t stream) {
   if (causal) return packed ? launch_insert_t<D, true, true>(a, grid, stream)
                             : launch_insert_t<D, true, false>(a, grid, stream);
   return packed ? launch_insert_t<D, false, true>(a, grid, stream)
@@ -548,9 +363,6 @@ hipError_t launch_insert(const InsertLaunch& p, hipStream_t stream) {
   a.heads_per_wg = a.n_rblk == 1 ? g : 1;
   const int groups8 = (a.n_tiles + 7) / 8 * 8;   // padded to a multiple of 8
   const dim3 grid((unsigned)((size_t)groups8 * (g / a.heads_per_wg) * a.n_rblk));
-  if (a.n_rblk > 1)   // S > 128
-    return p.D == 64 ? launch_insert_long_d<64>(a, grid, p.causal, p.packed, stream)
-                     : launch_insert_long_d<128>(a, grid, p.causal, p.packed, stream);
   return p.D == 64 ? launch_insert_d<64>(a, grid, p.causal, p.packed, stream)
                    : launch_insert_d<128>(a, grid, p.causal, p.packed, stream);
 }
