@@ -500,6 +500,11 @@ __global__ __launch_bounds__(kThreads) void finalize_top1_block_kernel(const Sea
 }
 
 // k > 1: pick the k best groups, re-score their rows, pick the k best rows.
+// Selecting the k best of n items takes k rounds of a workgroup-wide arg-max in general; while
+// the items fit one per thread (n <= 256: the common case once the groups are small) every
+// thread instead counts the items that rank before its own -- the order is total, so that count
+// is the item's position -- and the first k positions are written directly: one pass, two
+// barriers, no rounds.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void finalize_topk_kernel(const SearchArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -507,31 +512,71 @@ __global__ __launch_bounds__(kThreads) void finalize_topk_kernel(const SearchArg
   int* sel = reinterpret_cast<int*>(qf + a.E);         // [k] selected groups
   __shared__ float red_s[4];
   __shared__ int red_i[4];
+  typedef int i32x4 __attribute__((ext_vector_type(4)));
+  __shared__ __attribute__((aligned(16))) float item_s[kThreads];
+  __shared__ __attribute__((aligned(16))) int item_i[kThreads];
   const int b = blockIdx.x, tid = threadIdx.x;
   const int rpw = a.rows_per_wg;
   const T* q = reinterpret_cast<const T*>(a.q) + (size_t)b * a.E;
   for (int e = tid; e < a.E; e += kThreads) qf[e] = load_as_float(q + e);
 
+  // position of this thread's item (s, i) among the n <= 256 items held one per thread (threads
+  // without an item pass i = kIdxNone), and the number of items there are
+  auto position = [&](float s, int i, int n, int& n_items) {
+    item_s[tid] = s;
+    item_i[tid] = i;
+    __syncthreads();
+    int before = 0, count = 0;
+    // four items per read, no branches: every thread has stored an item (kIdxNone beyond n), so
+    // reading up to the next multiple of four is safe and the extra items do not count
+    for (int j = 0; j < n; j += 4) {
+      const f32x4 sj = *reinterpret_cast<const f32x4*>(item_s + j);
+      const i32x4 ij = *reinterpret_cast<const i32x4*>(item_i + j);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const bool there = ij[t] != kIdxNone;
+        count += there ? 1 : 0;
+        before += (there && ranks_before(sj[t], ij[t], s, i)) ? 1 : 0;
+      }
+    }
+    __syncthreads();   // the arrays are used again
+    n_items = count;
+    return before;
+  };
+
   // 1. the min(k, G) groups with the best maxima, in rank order
   const int ng = min(a.k, a.G);
-  float last_s = INFINITY;
-  int last_i = -1;
-  for (int r = 0; r < ng; ++r) {
+  if (a.G <= kThreads) {
+    if (tid < ng) sel[tid] = -1;   // fewer groups with a maximum than ng: the rest stay empty
     float s = -INFINITY;
     int i = kIdxNone;
-    for (int gi = tid; gi < a.G; gi += kThreads) {
-      const float so = a.part_s[(size_t)b * a.G + gi];
-      const int io = a.part_i[(size_t)b * a.G + gi];
-      // only groups ranked strictly after the previous pick
-      if (ranks_before(last_s, last_i, so, io) && ranks_before(so, io, s, i)) { s = so; i = io; }
+    if (tid < a.G) {
+      s = a.part_s[(size_t)b * a.G + tid];
+      i = a.part_i[(size_t)b * a.G + tid];
     }
-    block_argmax(s, i, red_s, red_i);
-    if (tid == 0) sel[r] = (i == kIdxNone) ? -1 : i / rpw;
-    last_s = s; last_i = i;
+    int n_items;
+    const int pos = position(s, i, a.G, n_items);
+    if (i != kIdxNone && pos < ng) sel[pos] = i / rpw;
+  } else {
+    float last_s = INFINITY;
+    int last_i = -1;
+    for (int r = 0; r < ng; ++r) {
+      float s = -INFINITY;
+      int i = kIdxNone;
+      for (int gi = tid; gi < a.G; gi += kThreads) {
+        const float so = a.part_s[(size_t)b * a.G + gi];
+        const int io = a.part_i[(size_t)b * a.G + gi];
+        // only groups ranked strictly after the previous pick
+        if (ranks_before(last_s, last_i, so, io) && ranks_before(so, io, s, i)) { s = so; i = io; }
+      }
+      block_argmax(s, i, red_s, red_i);
+      if (tid == 0) sel[r] = (i == kIdxNone) ? -1 : i / rpw;
+      last_s = s; last_i = i;
+    }
   }
   __syncthreads();
 
-  // 2. re-score every row of the selected groups
+  // 2. re-score every row of the selected groups, one row per thread
   float* cand = a.cand + (size_t)b * a.k * rpw;
   for (int slot = tid; slot < ng * rpw; slot += kThreads) {
     const int gsel = sel[slot / rpw];
@@ -544,7 +589,31 @@ __global__ __launch_bounds__(kThreads) void finalize_topk_kernel(const SearchArg
   __syncthreads();
 
   // 3. the k best rows among the candidates, in rank order
-  last_s = INFINITY; last_i = -1;
+  if (ng * rpw <= kThreads) {
+    float s = -INFINITY;
+    int i = kIdxNone;
+    if (tid < ng * rpw) {
+      const int gsel = sel[tid / rpw];
+      const int row = gsel * rpw + tid % rpw;
+      const float so = cand[tid];
+      if (gsel >= 0 && row < a.N && so == so) { s = so; i = row; }   // a NaN score never ranks
+    }
+    int n_items;
+    const int pos = position(s, i, ng * rpw, n_items);
+    if (i != kIdxNone && pos < a.k) {
+      a.idx[(size_t)b * a.k + pos] = i;
+      a.score[(size_t)b * a.k + pos] = s;
+      if (pos == 0) write_hit(a, b, s, i);
+    }
+    if (tid >= n_items && tid < a.k) {   // fewer rows than k ranked at all
+      a.idx[(size_t)b * a.k + tid] = -1;
+      a.score[(size_t)b * a.k + tid] = -INFINITY;
+      if (tid == 0) write_hit(a, b, -INFINITY, kIdxNone);
+    }
+    return;
+  }
+  float last_s = INFINITY;
+  int last_i = -1;
   for (int r = 0; r < a.k; ++r) {
     float s = -INFINITY;
     int i = kIdxNone;
