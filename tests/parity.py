@@ -36,7 +36,14 @@ def check_search(oracle, q, emb, k, theta, metric, map_of, gpu_idx, gpu_score, g
     for b in range(B):
         for r in range(k):
             s = float(o_score[b, r])
-            tol = REL_TIE * max(abs(s), 1e-30)
+            # fp32 accumulation error of an inner product is relative to its TERMS, sum |q_i e_i|
+            # <= |q| |e| (Cauchy-Schwarz), not to the score, which cancellation can bring near
+            # zero; the L2 score is a sum of non-negative terms and stays relative to itself
+            scale = abs(s)
+            if metric == 0:
+                qq0 = qn[b].astype(np.float64)
+                scale = max(scale, float(np.linalg.norm(qq0) * np.linalg.norm(en[o_idx[b, r]].astype(np.float64))))
+            tol = REL_TIE * max(scale, 1e-30)
             assert abs(float(g_score[b, r]) - s) <= tol, (b, r, g_score[b, r], s)
             if g_idx[b, r] == o_idx[b, r]:
                 continue

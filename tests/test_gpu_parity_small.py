@@ -319,6 +319,43 @@ def test_search_matches_oracle(ac, oracle_mod, case):
     assert exempt <= max(1, B * k // 50), exempt
 
 
+def _random_search_shapes(n, seed):
+    """Seeded shapes across every search path: sizes around the 32- and 128-row boundaries,
+    every feature width class, one to a few query blocks, k from 1 to the limit."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    for _ in range(n):
+        dt = torch.float16 if rng.random() < 0.8 else torch.float32
+        metric = "ip" if rng.random() < 0.8 else "l2"
+        E = int(rng.choice([16, 32, 40, 48, 64, 96, 128, 256, 512]))
+        N = int(rng.choice([1, 2, 31, 32, 33, 127, 128, 129, 255, 257, 1000, 1024, 2047, 4099]))
+        N += int(rng.integers(0, 3)) if N > 2 else 0
+        B = int(rng.choice([1, 2, 31, 32, 33, 64, 65, 100, 129]))
+        k = int(min(N, rng.choice([1, 1, 2, 3, 5, 8, 17, 64])))
+        shapes.append((N, E, B, k, dt, metric))
+    return shapes
+
+
+@pytest.mark.parametrize("case", _random_search_shapes(40, 20251128),
+                         ids=lambda c: "N%d-E%d-B%d-k%d-%s-%s" % (c[0], c[1], c[2], c[3],
+                                                                   str(c[4]).split(".")[-1], c[5]))
+def test_search_seeded_random_shapes_match_oracle(ac, oracle_mod, case):
+    N, E, B, k, dt, metric = case
+    g = _gen(7000 + 13 * N + 7 * E + B + k)
+    raw = torch.randn(N, E, generator=g)
+    emb = (raw / raw.norm(dim=-1, keepdim=True)).to(dt)
+    rows = torch.randint(0, N, (B,), generator=g)
+    qf = raw[rows] + 0.2 * torch.randn(B, E, generator=g)
+    qf[::4] = torch.randn(qf[::4].shape, generator=g)
+    q = (qf / qf.norm(dim=-1, keepdim=True)).to(dt)
+    m = ac.AC_IP if metric == "ip" else ac.AC_L2
+    theta = 0.8 if metric == "ip" else 0.4
+    map_of = torch.randint(0, 9, (N,), generator=g).int()
+    idx, score, hit = _run_search(ac, emb, q, k, theta, m, map_of=map_of)
+    exempt = parity.check_search(oracle_mod, q, emb, k, theta, m, map_of, idx, score, hit)
+    assert exempt <= max(1, B * k // 25), exempt
+
+
 NAN_CASES = [
     # N, E, B, k, dtype, metric: one per phase-1 kernel and finalising kernel
     (1000, 256, 8, 1, torch.float16, "ip"),      # row-stationary matrix-core kernel, k = 1
