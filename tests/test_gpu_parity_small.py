@@ -659,6 +659,87 @@ def test_insert_stores_the_oracles_map_and_output(ac, oracle_mod, case, layout, 
     db.close()
 
 
+def _random_attention_shapes(n, seed):
+    """Seeded shapes across the bf16 kernels' variants: resident and streaming lengths (ragged
+    row blocks and key chunks), both head widths, head groupings, layouts, padded batches."""
+    rng = np.random.default_rng(seed)
+    shapes = []
+    for _ in range(n):
+        S = int(rng.choice([32, 64, 96, 128, 160, 192, 256, 288, 352, 448]))
+        D = int(rng.choice([64, 128]))
+        Hkv = int(rng.choice([1, 2, 3]))
+        grp = int(rng.choice([1, 2, 4]))
+        L = int(rng.choice([1, 2]))
+        B = int(rng.choice([1, 2, 3]))
+        shapes.append((B, L, Hkv * grp, Hkv, S, D, bool(rng.random() < 0.6),
+                       "packed" if rng.random() < 0.6 else "dense", bool(rng.random() < 0.4)))
+    return shapes
+
+
+@pytest.mark.parametrize("case", _random_attention_shapes(24, 20251129),
+                         ids=lambda c: "B%d-L%d-H%d/%d-S%d-D%d-%s-%s-%s" % (
+                             c[0], c[1], c[2], c[3], c[4], c[5], "causal" if c[6] else "dense", c[7],
+                             "padded" if c[8] else "full"))
+def test_exact_insert_and_reuse_on_seeded_random_shapes(ac, oracle_mod, case):
+    # one chain per shape: exact attention, the same computed and remembered, and the reuse
+    # branch on the remembered maps, each against the oracle
+    B, L, Hq, Hkv, S, D, causal, layout, padded = case
+    M, E = B + 2, 32
+    g = _gen(1300 + 17 * S + D + 5 * Hq + B)
+    Q = torch.randn(B, L, Hq, S, D, generator=g).to(torch.bfloat16)
+    K = torch.randn(B, L, Hkv, S, D, generator=g).to(torch.bfloat16)
+    V = torch.randn(B, L, Hkv, S, D, generator=g).to(torch.bfloat16)
+    key_len = None
+    if padded:
+        key_len = torch.randint(1, S + 1, (B,), generator=g).int()
+        key_len[0] = S - 27 if S > 32 else S
+    kl = None if key_len is None else key_len.numpy()
+    ref, maps_ref = [], []
+    for l in range(L):
+        o, P = oracle_mod.attention_exact(parity.to_np(Q[:, l]), parity.to_np(K[:, l]), parity.to_np(V[:, l]),
+                                          causal=causal, return_map=True, key_len=kl)
+        ref.append(o)
+        maps_ref.append(oracle_mod.round_maps(P, oracle_mod.ROUND_BF16))
+
+    # exact attention (layers fold into heads)
+    O = torch.full((B, L * Hq, S, D), 7.0, dtype=torch.bfloat16, device="cuda")
+    ac.attention_exact(Q.view(B, L * Hq, S, D).cuda(), K.view(B, L * Hkv, S, D).cuda(),
+                       V.view(B, L * Hkv, S, D).cuda(), O, causal=causal,
+                       key_len=None if key_len is None else key_len.cuda())
+    torch.cuda.synchronize()
+    for l in range(L):
+        assert parity.max_abs_err(O[:, l * Hq:(l + 1) * Hq].contiguous(), ref[l]) <= 2e-2
+
+    # computed and remembered
+    tile = ac.packed_tile_elems(S, causal) if layout == "packed" else S * S
+    maps = torch.zeros(M, L, Hq, tile, dtype=torch.bfloat16, device="cuda")
+    emb = torch.zeros(M, E, dtype=torch.float16, device="cuda")
+    db = ac.attncache_build_db(emb, maps if layout == "packed" else maps.view(M, L, Hq, S, S),
+                               n_kv_heads=Hkv, head_dim=D, causal=causal, seq_len=S)
+    slot = torch.randperm(M, generator=g)[:B].int()
+    feat = torch.randn(B, E, generator=g).half()
+    O2 = torch.full((B, L, Hq, S, D), 7.0, dtype=torch.bfloat16, device="cuda")
+    ac.attncache_insert(db, Q.cuda(), K.cuda(), V.cuda(), O2, slot=slot.cuda(), feat=feat.cuda(),
+                        key_len=None if key_len is None else key_len.cuda())
+    torch.cuda.synchronize()
+    maps_h = parity.to_np(maps)
+    for l in range(L):
+        assert parity.max_abs_err(O2[:, l].contiguous(), ref[l]) <= 2e-2
+        for b in range(B):
+            for h in range(Hq):
+                stored = maps_h[int(slot[b]), l, h]
+                got = parity.unpack_map(stored, S, causal) if layout == "packed" else stored.reshape(S, S)
+                parity.check_stored_map(got, maps_ref[l][b, h])
+
+    # the reuse branch on what was remembered
+    O3 = torch.full((B, L, Hq, S, D), 7.0, dtype=torch.bfloat16, device="cuda")
+    ac.attncache_apply(db, slot.cuda(), V.cuda(), O3)
+    torch.cuda.synchronize()
+    for l in range(L):
+        assert parity.max_abs_err(O3[:, l].contiguous(), ref[l]) <= 2e-2
+    db.close()
+
+
 def test_insert_then_search_and_reuse_closes_the_loop(ac, oracle_mod):
     # miss -> compute and remember -> the same input hits and the reuse branch returns the
     # output the recompute branch produced (same rounded map, summed in another order)
