@@ -600,6 +600,9 @@ INSERT_CASES = [
     (2, 1, 2, 2, 160, 128, False),    # dense maps, ragged last chunk
     (2, 1, 2, 1, 512, 128, True),     # four row blocks, up to eight 64-key chunks, shared K and V
     (2, 2, 2, 2, 352, 64, False),     # dense maps, 32 keys in the last chunk, one wave in the last row block
+    (2, 1, 2, 2, 32, 64, True),       # a single 32-row block: one active wave, half a chunk of keys
+    (2, 1, 4, 1, 32, 128, False),     # the same, four heads on one K and V
+    (2, 1, 2, 2, 64, 128, True),      # exactly one chunk
 ]
 
 
@@ -617,7 +620,7 @@ def test_insert_stores_the_oracles_map_and_output(ac, oracle_mod, case, layout, 
     feat = torch.randn(B, E, generator=g).half()
     key_len = None
     if padded:       # a right-padded batch: the stored map must hold exact zeros in the padding
-        key_len = torch.tensor([S - 27, 33, S][:B], dtype=torch.int32)
+        key_len = torch.tensor([max(1, S - 27), min(33, S), S][:B], dtype=torch.int32)
         for b in range(B):
             K[b, :, :, key_len[b]:] = 3.0
             V[b, :, :, key_len[b]:] = 50.0
