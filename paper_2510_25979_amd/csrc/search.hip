@@ -576,8 +576,29 @@ __global__ __launch_bounds__(kThreads) void finalize_topk_kernel(const SearchArg
   }
   __syncthreads();
 
-  // 2. re-score every row of the selected groups, one row per thread
+  // 2. re-score every row of the selected groups, one row per thread -- or, when there are
+  // at most 128 (64) rows, two (four) threads per row, each walking its own contiguous part: a
+  // thread's walk is a chain of cache round trips, so the shorter the walk the better
   float* cand = a.cand + (size_t)b * a.k * rpw;
+  const int n_rows = ng * rpw;
+  const int tpr = (n_rows <= 64 && a.E % 4 == 0) ? 4 : ((n_rows <= 128 && a.E % 2 == 0) ? 2 : 1);
+  if (tpr > 1) {   // one trip: thread tid takes part tid % tpr of row tid / tpr
+    const int slot = tid / tpr, part = tid % tpr, seg = a.E / tpr;
+    float s = 0.f;
+    bool live = false;
+    if (slot < n_rows) {
+      const int gsel = sel[slot / rpw];
+      const int r = gsel * rpw + slot % rpw;
+      if (gsel >= 0 && r < a.N) {
+        live = true;
+        s = row_score(reinterpret_cast<const T*>(a.emb) + (size_t)r * a.E + part * seg, qf + part * seg,
+                      seg, a.metric);
+      }
+    }
+    s += __shfl_xor(s, 1);
+    if (tpr == 4) s += __shfl_xor(s, 2);
+    if (part == 0 && slot < n_rows) cand[slot] = live ? s : -INFINITY;
+  } else
   for (int slot = tid; slot < ng * rpw; slot += kThreads) {
     const int gsel = sel[slot / rpw];
     const int r = gsel * rpw + slot % rpw;
