@@ -358,18 +358,44 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
   };
 
   if constexpr (RESIDENT) {
-    // A fixed number of workgroups, each taking every gridDim.x-th tile: skipping a tile whose
-    // batch item was served by the reuse branch costs a scalar test instead of a workgroup
-    // launch, and the copies of the next tile's K and V are started before the last head of
-    // the current tile is written out, so stores and loads of one workgroup overlap.
+    // A fixed number of workgroups, each taking every gridDim.x-th tile: the copies of the next
+    // tile's K and V are started before the last head of the current tile is written out, so
+    // stores and loads of one workgroup overlap, and a tile whose batch item was served by the
+    // reuse branch costs no workgroup launch.  Which of its tiles have work a workgroup finds
+    // out 64 candidates at a time: lane i tests candidate i (one vector load of the routing
+    // flags, one round trip to memory for all of them) and the votes form a wave-uniform bit
+    // mask that the walk below consumes with scalar bit operations.
     const int hslots = g / a.heads_per_wg;
-    auto locate = [&](int from) {   // first tile at or after `from` (same stride) that has work
-      for (int t = from; t < a.n_blocks; t += gridDim.x) {
-        const int ut = ((t >> 3) / hslots) * 8 + (t & 7);   // ids equal mod 8 (one XCD) share K, V
-        if (ut < a.n_kvtiles && !(a.row_sel && a.row_sel[ut / a.Hkv] >= 0)) return t;
+    int cand_base = 0;          // candidates cand_base .. cand_base + 63 are in `live`
+    unsigned long long live = 0;
+    auto scan = [&](int base) {
+      // (tile numbers stay below 2^31 + 64 gridDim.x: unsigned 32-bit arithmetic is enough)
+      const unsigned t = blockIdx.x + (unsigned)(base + lane) * gridDim.x;
+      bool work = false;
+      if (t < (unsigned)a.n_blocks) {
+        const int ti = (int)t;
+        const int ut = ((ti >> 3) / hslots) * 8 + (ti & 7);   // ids equal mod 8 (one XCD) share K, V
+        work = ut < a.n_kvtiles && !(a.row_sel && a.row_sel[ut / a.Hkv] >= 0);
       }
-      return -1;
+      cand_base = base;
+      live = __ballot(work);
     };
+    // first tile with work among this workgroup's candidates number `from` and up, or -1
+    auto locate = [&](int from) {
+      while (true) {
+        const int shift = from - cand_base;
+        const unsigned long long rest = shift < 64 ? (live >> shift) : 0ull;
+        if (rest) {
+          const int i = from + __builtin_ctzll(rest);
+          return (int)(blockIdx.x + (unsigned)i * gridDim.x);
+        }
+        const int next = cand_base + 64;
+        if (blockIdx.x + (unsigned)next * gridDim.x >= (unsigned)a.n_blocks) return -1;
+        scan(next);
+        from = next;
+      }
+    };
+    scan(0);
     int h_first = 0;
     auto enter = [&](int t) {       // tile variables, and its K and V on their way
       const int slot = t >> 3;
@@ -385,8 +411,8 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
       prefetch(kb0, vb0, 0);
       if (n_chunk > 1) prefetch(kb1, vb1, 1);
     };
-    int t = locate(blockIdx.x);
-    if (t < 0) return;   // e.g. a batch served entirely by the reuse branch: a few scalar loads
+    int t = locate(0);
+    if (t < 0) return;   // e.g. a batch served entirely by the reuse branch
     enter(t);
     while (true) {
       publish();
@@ -408,7 +434,7 @@ __global__ __launch_bounds__(kThreads, (D == 64 ? 3 : 2)) void exact_bf16_kernel
       const float inv = 1.0f / (l_run + __shfl_xor(l_run, 32));
       bf16_t* Olast = reinterpret_cast<bf16_t*>(a.O) + (((size_t)b * a.Hq + h) * S + r0) * (size_t)D;
       const bool act = active;
-      const int tn = locate(t + gridDim.x);
+      const int tn = locate((t - (int)blockIdx.x) / (int)gridDim.x + 1);
       __syncthreads();          // every wave has finished reading the stages
       if (tn >= 0) enter(tn);
       if (act) store_small(Olast, inv);   // registers and the wave's own small buffer only
@@ -518,7 +544,18 @@ static hipError_t launch_exact_bf16_r(ExactArgs a, dim3 grid, hipStream_t stream
   // resident launch: at most 32 workgroups per compute unit walk the tiles (enough of them for
   // the hardware to even out an uneven mix of hits and misses -- fewer, longer-lived workgroups
   // measured 2-5 % slower; a multiple of 8 keeps a workgroup's tiles on its own XCD)
-  if (RESIDENT && grid.x > 8192u) grid.x = 8192u;
+  // The resident variant walks its tiles with a fixed number of workgroups.  Dispatching a
+  // workgroup takes time even when it finds nothing to do (some 420 workgroups start per
+  // microsecond: 8,192 of them cost the 19 us that a launch on a batch without misses used to
+  // take), so a routed launch, which may find little or nothing, gets half as many.  Fewer
+  // still would help that case more (2,048: 7 instead of 9 us) but costs a launch with many
+  // misses its load balance (64 of 128 items at the 8B shape: 4-9 % slower, the hardware
+  // balances many short-lived workgroups better than few long-lived ones); 4,096 costs nothing
+  // measurable there.
+  if (RESIDENT) {
+    const unsigned cap = a.row_sel ? 4096u : 8192u;
+    if (grid.x > cap) grid.x = cap;
+  }
   hipLaunchKernelGGL((exact_bf16_kernel<D, CAUSAL, RESIDENT>), grid, dim3(kThreads), 0, stream, a);
   return hipGetLastError();
 }
