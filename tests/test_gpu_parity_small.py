@@ -222,6 +222,40 @@ def test_exact_many_tiles_per_workgroup_with_routing(ac, oracle_mod):
     assert (O[[0, 5, 6, 32]] == 7.0).all()
 
 
+def test_exact_routed_walk_beyond_one_mask_of_candidates(ac, oracle_mod):
+    # A routed launch has at most 4,096 workgroups and a workgroup looks at 64 candidate tiles
+    # per scan of the routing flags: with more than 262,144 (item, head) tiles a walk needs a
+    # second scan.  Sampled tiles against the oracle (the first and last tiles, and tiles on both
+    # sides of the second scan), routed-away items untouched.
+    B, H, S, D = 2100, 128, 32, 64
+    assert B * H > 64 * 4096
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev).manual_seed(4711)
+    Q = torch.randn(B, H, S, D, generator=g, device=dev).to(torch.bfloat16)
+    K = torch.randn(B, H, S, D, generator=g, device=dev).to(torch.bfloat16)
+    V = torch.randn(B, H, S, D, generator=g, device=dev).to(torch.bfloat16)
+    away = torch.rand(B, generator=g, device=dev) < 0.5
+    away[[0, 2047, 2048, B - 1]] = torch.tensor([False, True, False, False], device=dev)
+    row_sel = torch.where(away, torch.ones(B, dtype=torch.int32, device=dev),
+                          -torch.ones(B, dtype=torch.int32, device=dev))
+    O = torch.full((B, H, S, D), 7.0, dtype=torch.bfloat16, device=dev)
+    ac.attention_exact(Q, K, V, O, row_sel=row_sel)
+    torch.cuda.synchronize()
+    assert (O[away] == 7.0).all()
+    live = (~away).nonzero().flatten().cpu().tolist()
+    rng = np.random.default_rng(5)
+    items = sorted({0, 2048, B - 1, live[len(live) // 2], *rng.choice(live, 12).tolist()})
+    for b in items:
+        heads = sorted({0, H - 1, *rng.integers(0, H, 3).tolist()})
+        ref = oracle_mod.attention_exact(parity.to_np(Q[b, heads]).reshape(1, len(heads), S, D),
+                                         parity.to_np(K[b, heads]).reshape(1, len(heads), S, D),
+                                         parity.to_np(V[b, heads]).reshape(1, len(heads), S, D))
+        assert parity.max_abs_err(O[b, heads].contiguous().unsqueeze(0), ref) <= 2e-2, b
+    # every tile of a live item was written (nothing kept the fill value in a whole tile)
+    untouched = (O[~away] == 7.0).flatten(2).all(-1)
+    assert not untouched.any()
+
+
 def test_exact_large_logits_stay_finite(ac, oracle_mod):
     # peaked softmax: logits of magnitude ~60 must not overflow the online rescaling
     B, H, S, D = 1, 2, 256, 64
