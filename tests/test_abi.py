@@ -65,6 +65,45 @@ def test_workspace_query_validates_without_a_gpu():
         binding.attncache_workspace_bytes(d, 64, 1)
 
 
+def test_workspace_sizes_follow_the_search_plan():
+    """Workspace = one (score, row) pair per query and group (padded to 256 bytes) + k groups of
+    candidate scores per query for k > 1 + 256 bytes; the group size depends on the path the
+    shape takes.  Pure host logic."""
+    from paper_2510_25979_amd import binding
+
+    def ws(N, E, B, k, dtype=None, metric=None):
+        d = binding.DbDesc(n_emb=N, emb_dim=E, emb_dtype=binding.AC_F16 if dtype is None else dtype,
+                           metric=binding.AC_IP if metric is None else metric,
+                           n_entries=N, n_layers=1, n_q_heads=1, n_kv_heads=1, head_dim=64,
+                           seq_len=32, map_dtype=binding.AC_BF16, causal=1, maps_on_host=0, map_layout=0)
+        return binding.attncache_workspace_bytes(d, B, k)
+
+    def expect(B, G, k, rpw):
+        part = (B * G * 8 + 255) // 256 * 256
+        return part + (B * k * rpw * 4 if k > 1 else 0) + 256
+
+    # The size is the larger of what the inner-product and the L2 path of the shape need (the
+    # metric is a property of the handle, not of the query): the vector-ALU path has groups of
+    # 256 rows.
+    def both(B, N, k, rpw_ip):
+        return max(expect(B, -(-N // rpw_ip), k, rpw_ip), expect(B, -(-N // 256), k, 256))
+
+    # matrix-core path, top-1, small database: one group per 128-row workgroup
+    assert ws(10000, 256, 64, 1) == both(64, 10000, 1, 128)
+    # matrix-core path, top-k, small database: groups of 32 rows (the long-sequence workload's search)
+    assert ws(1024, 512, 16, 4) == both(16, 1024, 4, 32)
+    assert ws(32768, 128, 9, 5) == both(9, 32768, 5, 32)
+    # just above the limit of the small-group plan: back to one group per workgroup
+    assert ws(40000, 256, 10, 3) == both(10, 40000, 3, 128)
+    # million-row index: ~480 groups of a multiple of 64 rows
+    rpw = 64 * -(-1000000 // (64 * 480))
+    assert ws(1000000, 256, 256, 1) == both(256, 1000000, 1, rpw)
+    # fp32 features: vector-ALU path only
+    assert ws(1024, 128, 4, 3, dtype=binding.AC_F32) == expect(4, 4, 3, 256)
+    # monotone in the batch
+    assert ws(10000, 256, 128, 1) > ws(10000, 256, 64, 1)
+
+
 def test_product_path_does_not_touch_the_oracle():
     pkg = os.path.join(ROOT, "paper_2510_25979_amd")
     for dirpath, _, files in os.walk(pkg):
